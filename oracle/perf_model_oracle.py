@@ -1,0 +1,73 @@
+"""Oracle for the roofline performance model.  TEST INFRASTRUCTURE ONLY.
+
+Section 2.2 written out in plain fp64 Python, in the section's order:
+
+    t_dense          = C / F
+    t_sparse_compute = alpha * x * C / F
+    t_sparse_bw      = (S_A + beta * x * S_W) / B
+    speedup          = t_dense / max(t_sparse_compute, t_sparse_bw)
+
+C is the FLOP count of the dense convolution, S_A the bytes of the input and
+output activations, S_W the bytes of the dense weights (all three "without
+considering sparsity"), x the nonzero density, F and B the achievable FLOP/s and
+memory bandwidth, alpha the compute overhead of the sparse kernel, beta the
+storage overhead of its format.  The upper bound of useful sparsity is the x at
+which the two sparse times are equal; the lower bound is x = 1/alpha.
+
+Readings where the section leaves something open: C counts a multiply-add as
+two FLOPs over the whole batch; S_A counts each unpadded activation once;
+S_W counts each dense weight once per call.  With Table 1's F and B these
+reproduce the section's own worked numbers (the pins in the tests).
+
+When alpha is not given it is derived for a machine whose sparse kernel is
+limited by either its vector multiply-add rate or the bandwidth of the on-chip
+memory its operands are read from:
+
+    F_sparse = lane_efficiency * min(fma_flops, 2 * lds_bytes_per_s / lds_bytes_per_fma)
+    alpha    = F / F_sparse
+"""
+from __future__ import annotations
+
+import math
+
+
+def layer_counts(layer, N: int):
+    Cg = layer.C // layer.groups
+    OH = (layer.H + 2 * layer.pad - layer.R) // layer.stride + 1
+    OW = (layer.W + 2 * layer.pad - layer.S) // layer.stride + 1
+    flops = 2.0 * layer.K * Cg * layer.R * layer.S * OH * OW * N
+    s_a = 4.0 * N * (layer.C * layer.H * layer.W + layer.K * OH * OW)
+    s_w = 4.0 * layer.K * Cg * layer.R * layer.S
+    return flops, s_a, s_w
+
+
+def derive_alpha(F, fma_flops, lds_bytes_per_s, lds_bytes_per_fma, lane_efficiency):
+    f_sparse = lane_efficiency * min(fma_flops, 2.0 * lds_bytes_per_s / lds_bytes_per_fma)
+    return F / f_sparse
+
+
+def predict(layer, N: int, x: float, F: float, B: float, alpha: float, beta: float = 2.0):
+    flops, s_a, s_w = layer_counts(layer, N)
+    t_dense = flops / F
+    t_sc = alpha * x * flops / F
+    t_sbw = (s_a + beta * x * s_w) / B
+    t_sparse = max(t_sc, t_sbw)
+    # density at which compute time equals bandwidth time
+    denom = alpha * flops / F - beta * s_w / B
+    x_upper = (s_a / B) / denom if denom > 0 else math.inf
+    return {
+        "flops_dense": flops,
+        "bytes_act": s_a,
+        "bytes_w": s_w,
+        "alpha": alpha,
+        "t_dense": t_dense,
+        "t_sparse_compute": t_sc,
+        "t_sparse_bw": t_sbw,
+        "t_sparse": t_sparse,
+        "speedup": t_dense / t_sparse,
+        "effective_flops": flops / t_sparse,
+        "actual_flops": x * flops / t_sparse,
+        "x_upper": x_upper,
+        "x_lower": 1.0 / alpha,
+        "bandwidth_bound": t_sbw > t_sc,
+    }

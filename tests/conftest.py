@@ -1,0 +1,24 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_collection_modifyitems(config, items):
+    # GPU tests print what they are about to run, so a fault names its case.
+    pass
+
+
+@pytest.fixture(scope="session")
+def oracle():
+    from oracle import sconv_oracle
+    sconv_oracle.build()
+    return sconv_oracle

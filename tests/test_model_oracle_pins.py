@@ -1,0 +1,79 @@
+"""Pins for the performance-model oracle: the numbers Section 2.2 and
+Section 3.2 print, read from tests/golden/paper_model_values.txt."""
+import math
+import os
+
+import pytest
+
+from oracle import perf_model_oracle as pm
+from paper_1608_01409_amd import workloads as wl
+
+GOLD = {}
+with open(os.path.join(os.path.dirname(__file__), "golden", "paper_model_values.txt")) as fh:
+    for line in fh:
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            GOLD[line[0]] = float(line[1])
+
+CONV5 = wl.LAYERS["conv5"]
+
+
+def test_conv5_counts_closed_form():
+    flops, s_a, s_w = pm.layer_counts(CONV5, 1)
+    assert flops == 2 * 256 * 192 * 9 * 169
+    assert s_a == 4 * (384 * 169 + 256 * 169)
+    assert s_w == 4 * 256 * 192 * 9
+
+
+@pytest.mark.parametrize("plat", ["bdw", "atom"])
+def test_upper_bound_of_useful_sparsity_matches_paper(plat):
+    F, B = GOLD[f"{plat}_sgemm_gflops"] * 1e9, GOLD[f"{plat}_bw_gbs"] * 1e9
+    p = pm.predict(CONV5, 1, 0.1, F, B, GOLD[f"{plat}_alpha"], GOLD["beta"])
+    # the paper prints one significant digit
+    assert round(p["x_upper"], 2) == GOLD[f"{plat}_conv5_x_upper"]
+    # at x_upper the two sparse times are equal by definition
+    q = pm.predict(CONV5, 1, p["x_upper"], F, B, GOLD[f"{plat}_alpha"], GOLD["beta"])
+    assert math.isclose(q["t_sparse_compute"], q["t_sparse_bw"], rel_tol=1e-12)
+
+
+def test_lower_bound_is_one_over_alpha():
+    p = pm.predict(CONV5, 144, 0.1, GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"])
+    assert round(p["x_lower"], 1) == GOLD["bdw_x_lower"]
+    q = pm.predict(CONV5, 144, p["x_lower"], GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"])
+    assert math.isclose(q["speedup"], 1.0, rel_tol=1e-12)
+
+
+def test_projected_speedup_range_and_measured_point():
+    F, B, a = GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"]
+    lo = pm.predict(CONV5, 144, 0.15, F, B, a)["speedup"]
+    hi = pm.predict(CONV5, 144, 0.05, F, B, a)["speedup"]
+    assert round(lo) == GOLD["bdw_conv5_speedup_lo"] and round(hi) == GOLD["bdw_conv5_speedup_hi"]
+    # measured 3.4x at x = 0.09 against the compute-bound projection 1/(alpha x)
+    s = pm.predict(CONV5, 144, 0.09, F, B, a)["speedup"]
+    assert math.isclose(s, 1 / (a * 0.09), rel_tol=1e-12)
+    assert abs(s - GOLD["bdw_measured_speedup_x009"]) / GOLD["bdw_measured_speedup_x009"] < 0.15
+
+
+def test_no_further_speedup_below_upper_bound_and_monotone_time():
+    F, B, a = GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"]
+    xs = [0.001, 0.005, 0.01, 0.02, 0.05, 0.1, 0.3, 0.5, 1.0]
+    ps = [pm.predict(CONV5, 1, x, F, B, a) for x in xs]
+    ts = [p["t_sparse"] for p in ps]
+    assert all(t2 >= t1 for t1, t2 in zip(ts, ts[1:]))
+    xu = ps[0]["x_upper"]
+    below = [p for p, x in zip(ps, xs) if x < xu]
+    assert all(p["bandwidth_bound"] for p in below)
+    # speedup saturates: halving x below the bound gains < 5 %
+    s1 = pm.predict(CONV5, 1, xu / 2, F, B, a)["speedup"]
+    s2 = pm.predict(CONV5, 1, xu / 4, F, B, a)["speedup"]
+    assert s2 / s1 < 1.05
+    # effective = actual / density
+    p = ps[5]
+    assert math.isclose(p["effective_flops"] * 0.1, p["actual_flops"], rel_tol=1e-12)
+
+
+def test_derived_alpha():
+    a = pm.derive_alpha(F=100e12, fma_flops=80e12, lds_bytes_per_s=80e12, lds_bytes_per_fma=4.0, lane_efficiency=0.8)
+    assert math.isclose(a, 100e12 / (0.8 * 40e12))
+    a = pm.derive_alpha(F=100e12, fma_flops=30e12, lds_bytes_per_s=80e12, lds_bytes_per_fma=4.0, lane_efficiency=1.0)
+    assert math.isclose(a, 100 / 30)
