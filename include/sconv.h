@@ -1,0 +1,175 @@
+/*
+ * sconv -- direct sparse convolution on MI355X (gfx950), C ABI.
+ *
+ * The operation (Section 2.1, Eq. (1) and Figure 2 of "Faster CNNs with Direct
+ * Sparse Convolutions and Guided Pruning"; batch, stride, zero padding and
+ * groups added):
+ *
+ *   out[n,k,y,x] = sum over the stored nonzeros j of CSR row k of
+ *                  value[j] * in_pad[n, off[j] + y*stride*Wp + x*stride]
+ *
+ * The pruned weights of a layer are a CSR matrix with one row per output
+ * channel k and one column per (c, r, s), c being the input channel inside the
+ * row's group.  Each column index is lowered once, on the host, to the offset
+ * off = ((g*Cg + c)*Hp + r)*Wp + s of element (c, r, s) in the zero-padded CHW
+ * image (Hp = H + 2*pad, Wp = W + 2*pad, g = k / (K/groups), Cg = C/groups).
+ * No im2col buffer and no dense weight matrix is ever formed.
+ *
+ * All functions return 0 (SCONV_OK) or a negative sconv_status; they never
+ * throw and keep no global state.  Distinct handles may be used from distinct
+ * threads.  Pointers marked [host] are read or written on the CPU during the
+ * call; pointers marked [device] are HIP device addresses that must stay valid
+ * until the stream work enqueued by the call has finished.
+ */
+#ifndef SCONV_H
+#define SCONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SCONV_OK = 0,
+    SCONV_ERR_NULL = -1,        /* a required pointer is NULL */
+    SCONV_ERR_DESC = -2,        /* non-positive size, groups not dividing C or K, output smaller than 1x1 */
+    SCONV_ERR_CSR = -3,         /* rowptr not starting at 0 / not monotone, column out of range or not strictly ascending */
+    SCONV_ERR_BATCH = -4,       /* N < 1 */
+    SCONV_ERR_CAPACITY = -5,    /* caller's buffer too small (export) */
+    SCONV_ERR_PLAN = -6,        /* a tiling the kernels cannot run was requested */
+    SCONV_ERR_HIP = -7,         /* a HIP call failed; sconv_last_hip_error() has its code */
+    SCONV_ERR_NOMEM = -8,       /* host allocation failed */
+    SCONV_ERR_RANGE = -9        /* sizes overflow 32-bit offsets inside one image */
+} sconv_status;
+
+/* Layer geometry (Section 2.1's problem statement).  The batch size is per call. */
+typedef struct {
+    int32_t C, H, W;            /* input channels, height, width (unpadded) */
+    int32_t K, R, S;            /* output channels (filters), filter height, width */
+    int32_t stride, pad, groups;
+} sconv_desc;
+
+/*
+ * How the kernels tile a layer.  Zero in every field asks the library to choose.
+ * kernel: 1 = LDS-tiled kernel (stride 1), 2 = direct kernel (any stride).
+ * For the LDS-tiled kernel one workgroup owns `nt` images (1, or a multiple of
+ * 4) and `waves/cg * rows_w` CSR rows; it walks the input channels in blocks of
+ * `cb`; each wave keeps rows_w x t x (4 if nt >= 4 else 1) accumulators per lane.
+ */
+typedef struct {
+    int32_t kernel, nt, cb, waves, cg, rows_w, t;
+} sconv_plan;
+
+typedef struct sconv_csr sconv_csr; /* opaque, owned by the library */
+
+/*
+ * Compress pruned dense weights [host] laid out [K][C/groups][R][S] into CSR,
+ * lower the column indices to offsets, and pack for the kernels.  Entries equal
+ * to zero (either sign) are dropped; every other value (denormal, NaN, Inf) is
+ * kept.  Host work only: device copies are made by the first sconv_forward.
+ * `plan` may be NULL.  On success *out receives a handle to free with
+ * sconv_destroy_csr.
+ */
+int sconv_create_csr(const sconv_desc *desc, const float *dense_w, const sconv_plan *plan, sconv_csr **out);
+
+/*
+ * Same, from caller-built CSR arrays [host] (Figure 2's rowptr / colidx /
+ * value): rowptr[K+1] with rowptr[0] == 0, colidx[nnz] in [0, (C/groups)*R*S)
+ * strictly ascending inside each row and equal to (c*R + r)*S + s, values[nnz]
+ * kept exactly as given (explicit zeros included).  The arrays are copied.
+ */
+int sconv_create_csr_from_arrays(const sconv_desc *desc, const int32_t *rowptr, const int32_t *colidx,
+                                 const float *values, const sconv_plan *plan, sconv_csr **out);
+
+/* Sizes and the tiling in use.  Any output pointer may be NULL. */
+int sconv_csr_info(const sconv_csr *h, int64_t *nnz, int32_t *out_h, int32_t *out_w, sconv_plan *plan);
+
+/*
+ * Canonical lowered CSR (Figure 2's arrays after lowering): rowptr[K+1],
+ * off[nnz] ascending in each row, values[nnz], all [host], caller-allocated.
+ * *nnz_io holds the capacity of off/values on entry and the count on return
+ * (SCONV_ERR_CAPACITY if too small; the count is still returned).
+ */
+int sconv_csr_export(const sconv_csr *h, int32_t *rowptr, int32_t *off, float *values, int64_t *nnz_io);
+
+/*
+ * Undo the kernel packing: walks the packed (reordered, channel-blocked,
+ * byte-offset) arrays the kernels read and rebuilds canonical lowered CSR from
+ * them alone.  `which` = 1 for the LDS-tiled kernel's arrays (SCONV_ERR_PLAN if
+ * the handle has none), 2 for the direct kernel's.  Same conventions as
+ * sconv_csr_export.  Equality of the two exports shows the packing loses and
+ * invents nothing.
+ */
+int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t *off, float *values, int64_t *nnz_io);
+
+/*
+ * out[N][K][OH][OW] = sparse convolution of in[N][C][H][W], both [device],
+ * contiguous fp32; `in` is NOT padded (padding is applied on chip).  `out` is
+ * overwritten, rows without nonzeros with zeros.  Enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream) of the current device and not
+ * waited for.  `in` and `out` must not overlap.
+ */
+int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream);
+
+/* The last HIP error code seen by a call on this handle (0 if none). */
+int sconv_last_hip_error(const sconv_csr *h);
+
+void sconv_destroy_csr(sconv_csr *h);
+
+const char *sconv_strerror(int status);
+
+/* ---- roofline performance model (Section 2.2) ------------------------------ */
+
+/*
+ * Machine parameters.  dense_flops (F) and hbm_bytes_per_s (B) are ACHIEVABLE
+ * rates, as the paper takes them from SGEMM and STREAM.  alpha > 0 is used as
+ * given (the paper's form); alpha <= 0 derives it from the ceilings of the
+ * sparse kernel:
+ *   F_sparse = lane_efficiency * min(fma_flops, 2 * lds_bytes_per_s / lds_bytes_per_fma)
+ *   alpha    = dense_flops / F_sparse
+ */
+typedef struct {
+    double dense_flops;       /* F, FLOP/s of dense convolution (GEMM proxy) */
+    double hbm_bytes_per_s;   /* B */
+    double alpha;             /* compute overhead of the sparse kernel, or <= 0 */
+    double beta;              /* storage overhead of CSR: 2 (4 B index per 4 B value) */
+    double fma_flops;         /* FP32 multiply-add ceiling of the sparse kernel, FLOP/s */
+    double lds_bytes_per_s;   /* LDS read bandwidth, whole chip */
+    double lds_bytes_per_fma; /* LDS bytes read per multiply-add (4: one fp32 operand) */
+    double lane_efficiency;   /* useful fraction of the lanes' multiply-adds */
+} sconv_machine;
+
+typedef struct {
+    double flops_dense;       /* C: 2*K*Cg*R*S*OH*OW*N */
+    double bytes_act;         /* S_A: 4*N*(C*H*W + K*OH*OW) */
+    double bytes_w;           /* S_W: 4*K*Cg*R*S */
+    double density;           /* x used (the handle's realised density if one was given) */
+    double alpha;             /* alpha used */
+    double t_dense;           /* C/F, seconds */
+    double t_sparse_compute;  /* alpha*x*C/F */
+    double t_sparse_bw;       /* (S_A + beta*x*S_W)/B */
+    double t_sparse;          /* max of the two */
+    double speedup;           /* t_dense / t_sparse */
+    double effective_flops;   /* C / t_sparse (zeros counted) */
+    double actual_flops;      /* x*C / t_sparse (nonzeros only) */
+    double x_upper;           /* density where t_sparse_compute == t_sparse_bw (inf if never) */
+    double x_lower;           /* 1/alpha: above it sparse is slower than dense */
+    int32_t bandwidth_bound;  /* 1 if t_sparse_bw > t_sparse_compute */
+} sconv_prediction;
+
+/* Measured defaults for one MI355X. */
+void sconv_machine_gfx950(sconv_machine *m);
+
+/*
+ * Evaluate the model for a layer at batch N and density x.  If `h` is not NULL
+ * its realised density nnz/(K*Cg*R*S) replaces `density`.  `m` NULL = the
+ * gfx950 defaults.  Pure host arithmetic.
+ */
+int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
+                        const sconv_machine *m, sconv_prediction *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCONV_H */

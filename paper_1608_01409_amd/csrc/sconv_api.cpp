@@ -1,0 +1,276 @@
+// The extern "C" surface of libsconv (see include/sconv.h) and the roofline model of Section 2.2.
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+
+#include "sconv_internal.h"
+
+using namespace sconv;
+
+struct sconv_csr {
+    sconv_desc desc;
+    Canonical canon;
+    sconv_plan requested;    // what the caller asked for (zeros = choose)
+    bool has_lds = false;
+    PackedLds lds;
+    PackedDirect direct;
+    DeviceLds dev_lds;
+    DeviceDirect dev_direct;
+    bool lds_uploaded = false, direct_uploaded = false;
+    int hip_err = 0;
+};
+
+static int finish_create(sconv_csr *h, const sconv_plan *plan)
+{
+    std::memset(&h->requested, 0, sizeof(h->requested));
+    if (plan) h->requested = *plan;
+    if (h->requested.kernel < 0 || h->requested.kernel > 2) return SCONV_ERR_PLAN;
+    const sconv_desc &d = h->desc;
+    const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
+    int rc = pack_direct(d, h->canon, h->direct);
+    if (rc) return rc;
+    if (h->requested.kernel != 2 && d.stride == 1) {
+        LdsTiling t;
+        // the automatic choice is tuned for large batches; small ones go to the direct kernel
+        rc = make_lds_tiling(d, h->requested, h->requested.nt ? h->requested.nt : 256, avg, t);
+        if (rc == SCONV_OK) {
+            rc = pack_lds(d, h->canon, t, h->lds);
+            if (rc) return rc;
+            h->has_lds = true;
+        } else if (h->requested.kernel == 1) {
+            return rc;
+        }
+    } else if (h->requested.kernel == 1) {
+        return SCONV_ERR_PLAN;
+    }
+    return SCONV_OK;
+}
+
+extern "C" int sconv_create_csr(const sconv_desc *desc, const float *dense_w, const sconv_plan *plan, sconv_csr **out)
+{
+    if (!desc || !dense_w || !out) return SCONV_ERR_NULL;
+    *out = nullptr;
+    int rc = validate_desc(*desc);
+    if (rc) return rc;
+    sconv_csr *h = new (std::nothrow) sconv_csr();
+    if (!h) return SCONV_ERR_NOMEM;
+    try {
+        h->desc = *desc;
+        rc = build_canonical_from_dense(*desc, dense_w, h->canon);
+        if (!rc) rc = finish_create(h, plan);
+    } catch (const std::bad_alloc &) {
+        rc = SCONV_ERR_NOMEM;
+    }
+    if (rc) {
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_create_csr_from_arrays(const sconv_desc *desc, const int32_t *rowptr, const int32_t *colidx,
+                                            const float *values, const sconv_plan *plan, sconv_csr **out)
+{
+    if (!desc || !rowptr || !out) return SCONV_ERR_NULL;
+    *out = nullptr;
+    int rc = validate_desc(*desc);
+    if (rc) return rc;
+    sconv_csr *h = new (std::nothrow) sconv_csr();
+    if (!h) return SCONV_ERR_NOMEM;
+    try {
+        h->desc = *desc;
+        rc = build_canonical_from_arrays(*desc, rowptr, colidx, values, h->canon);
+        if (!rc) rc = finish_create(h, plan);
+    } catch (const std::bad_alloc &) {
+        rc = SCONV_ERR_NOMEM;
+    }
+    if (rc) {
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_csr_info(const sconv_csr *h, int64_t *nnz, int32_t *out_h, int32_t *out_w, sconv_plan *plan)
+{
+    if (!h) return SCONV_ERR_NULL;
+    const Geometry g = geometry(h->desc);
+    if (nnz) *nnz = (int64_t)h->canon.val.size();
+    if (out_h) *out_h = g.OH;
+    if (out_w) *out_w = g.OW;
+    if (plan) {
+        std::memset(plan, 0, sizeof(*plan));
+        if (h->has_lds)
+            *plan = h->lds.t.p;
+        else
+            plan->kernel = 2;
+    }
+    return SCONV_OK;
+}
+
+static int export_canonical(const sconv_desc &d, const Canonical &c, int32_t *rowptr, int32_t *off, float *values,
+                            int64_t *nnz_io)
+{
+    if (!nnz_io) return SCONV_ERR_NULL;
+    const int64_t nnz = (int64_t)c.val.size();
+    const int64_t cap = *nnz_io;
+    *nnz_io = nnz;
+    if (cap < nnz) return SCONV_ERR_CAPACITY;
+    if (!rowptr || (nnz > 0 && (!off || !values))) return SCONV_ERR_NULL;
+    std::memcpy(rowptr, c.rowptr.data(), sizeof(int32_t) * (d.K + 1));
+    if (nnz) {
+        std::memcpy(off, c.off.data(), sizeof(int32_t) * nnz);
+        std::memcpy(values, c.val.data(), sizeof(float) * nnz);
+    }
+    return SCONV_OK;
+}
+
+extern "C" int sconv_csr_export(const sconv_csr *h, int32_t *rowptr, int32_t *off, float *values, int64_t *nnz_io)
+{
+    if (!h) return SCONV_ERR_NULL;
+    return export_canonical(h->desc, h->canon, rowptr, off, values, nnz_io);
+}
+
+extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t *off, float *values,
+                                int64_t *nnz_io)
+{
+    if (!h) return SCONV_ERR_NULL;
+    Canonical c;
+    int rc;
+    try {
+        if (which == 1) {
+            if (!h->has_lds) return SCONV_ERR_PLAN;
+            rc = unpack_lds(h->desc, h->lds, c);
+        } else if (which == 2) {
+            rc = unpack_direct(h->desc, h->direct, c);
+        } else {
+            return SCONV_ERR_PLAN;
+        }
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    if (rc) return rc;
+    return export_canonical(h->desc, c, rowptr, off, values, nnz_io);
+}
+
+extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream)
+{
+    if (!h || !in || !out) return SCONV_ERR_NULL;
+    if (N < 1) return SCONV_ERR_BATCH;
+    bool use_lds = h->has_lds;
+    if (use_lds && h->requested.kernel == 0 && N < 4 && h->lds.t.p.nt >= 4) use_lds = false;
+    int rc;
+    if (use_lds) {
+        if (!h->lds_uploaded) {
+            rc = upload(h->lds.pairs.data(), h->lds.pairs.size() * 8, &h->dev_lds.pairs, &h->hip_err);
+            if (!rc) rc = upload(h->lds.seg_ptr.data(), h->lds.seg_ptr.size() * 4, &h->dev_lds.seg_ptr, &h->hip_err);
+            if (!rc) rc = upload(h->lds.row_of.data(), h->lds.row_of.size() * 4, &h->dev_lds.row_of, &h->hip_err);
+            if (rc) return rc;
+            h->lds_uploaded = true;
+        }
+        return launch_lds(h->desc, h->lds.t, h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+    }
+    if (!h->direct_uploaded) {
+        rc = upload(h->direct.rowptr.data(), h->direct.rowptr.size() * 4, &h->dev_direct.rowptr, &h->hip_err);
+        if (!rc) rc = upload(h->direct.trip.data(), h->direct.trip.size() * 4, &h->dev_direct.trip, &h->hip_err);
+        if (rc) return rc;
+        h->direct_uploaded = true;
+    }
+    return launch_direct(h->desc, h->dev_direct, in, out, N, hip_stream, &h->hip_err);
+}
+
+extern "C" int sconv_last_hip_error(const sconv_csr *h) { return h ? h->hip_err : 0; }
+
+extern "C" void sconv_destroy_csr(sconv_csr *h)
+{
+    if (!h) return;
+    release(h->dev_lds.pairs);
+    release(h->dev_lds.seg_ptr);
+    release(h->dev_lds.row_of);
+    release(h->dev_direct.rowptr);
+    release(h->dev_direct.trip);
+    delete h;
+}
+
+extern "C" const char *sconv_strerror(int status)
+{
+    switch (status) {
+    case SCONV_OK: return "ok";
+    case SCONV_ERR_NULL: return "a required pointer is NULL";
+    case SCONV_ERR_DESC: return "bad layer descriptor";
+    case SCONV_ERR_CSR: return "malformed CSR arrays";
+    case SCONV_ERR_BATCH: return "batch size must be at least 1";
+    case SCONV_ERR_CAPACITY: return "output buffer too small";
+    case SCONV_ERR_PLAN: return "tiling not runnable for this layer";
+    case SCONV_ERR_HIP: return "HIP call failed";
+    case SCONV_ERR_NOMEM: return "out of host memory";
+    case SCONV_ERR_RANGE: return "sizes exceed 32-bit offsets";
+    default: return "unknown status";
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Section 2.2: t_dense = C/F, t_sparse_compute = alpha*x*C/F, t_sparse_bw = (S_A + beta*x*S_W)/B,
+// speedup = t_dense / max(t_sparse_compute, t_sparse_bw).
+
+extern "C" void sconv_machine_gfx950(sconv_machine *m)
+{
+    if (!m) return;
+    // Achievable rates measured on one MI355X (see the benchmark report); not data-sheet peaks.
+    m->dense_flops = 100e12;        // fp32 dense convolution / SGEMM proxy
+    m->hbm_bytes_per_s = 4.0e12;    // device copy kernel
+    m->alpha = 0.0;                 // derive from the ceilings below
+    m->beta = 2.0;
+    m->fma_flops = 73.5e12;         // v_fma_f32, 256 CUs x 60 lanes-FMA/clk x 2.4 GHz x 2
+    m->lds_bytes_per_s = 148e12;    // aligned ds_read_b128, 242 B/clk/CU
+    m->lds_bytes_per_fma = 4.0;
+    m->lane_efficiency = 0.80;
+}
+
+extern "C" int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
+                                   const sconv_machine *m, sconv_prediction *out)
+{
+    if (!desc || !out) return SCONV_ERR_NULL;
+    int rc = validate_desc(*desc);
+    if (rc) return rc;
+    if (N < 1) return SCONV_ERR_BATCH;
+    sconv_machine def;
+    if (!m) {
+        sconv_machine_gfx950(&def);
+        m = &def;
+    }
+    const Geometry g = geometry(*desc);
+    const double cols = (double)g.Cg * desc->R * desc->S;
+    double x = density;
+    if (h) x = (double)h->canon.val.size() / ((double)desc->K * cols);
+    if (!(x >= 0.0) || !(m->dense_flops > 0) || !(m->hbm_bytes_per_s > 0)) return SCONV_ERR_DESC;
+    double alpha = m->alpha;
+    if (!(alpha > 0)) {
+        const double lds_flops = 2.0 * m->lds_bytes_per_s / m->lds_bytes_per_fma;
+        const double f_sparse = m->lane_efficiency * std::fmin(m->fma_flops, lds_flops);
+        if (!(f_sparse > 0)) return SCONV_ERR_DESC;
+        alpha = m->dense_flops / f_sparse;
+    }
+    sconv_prediction p;
+    p.flops_dense = 2.0 * desc->K * cols * g.OH * g.OW * N;
+    p.bytes_act = 4.0 * N * ((double)desc->C * desc->H * desc->W + (double)desc->K * g.OH * g.OW);
+    p.bytes_w = 4.0 * desc->K * cols;
+    p.density = x;
+    p.alpha = alpha;
+    p.t_dense = p.flops_dense / m->dense_flops;
+    p.t_sparse_compute = alpha * x * p.flops_dense / m->dense_flops;
+    p.t_sparse_bw = (p.bytes_act + m->beta * x * p.bytes_w) / m->hbm_bytes_per_s;
+    p.t_sparse = std::fmax(p.t_sparse_compute, p.t_sparse_bw);
+    p.speedup = p.t_dense / p.t_sparse;
+    p.effective_flops = p.flops_dense / p.t_sparse;
+    p.actual_flops = x * p.flops_dense / p.t_sparse;
+    const double denom = alpha * p.flops_dense / m->dense_flops - m->beta * p.bytes_w / m->hbm_bytes_per_s;
+    p.x_upper = denom > 0 ? (p.bytes_act / m->hbm_bytes_per_s) / denom : std::numeric_limits<double>::infinity();
+    p.x_lower = 1.0 / alpha;
+    p.bandwidth_bound = p.t_sparse_bw > p.t_sparse_compute ? 1 : 0;
+    *out = p;
+    return SCONV_OK;
+}

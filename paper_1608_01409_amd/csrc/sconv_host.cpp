@@ -1,0 +1,410 @@
+// Host side of libsconv: descriptor and CSR validation, canonical offset lowering
+// (Figure 2's colidx -> f(c,r,s)), choice of a tiling, and packing of the nonzeros
+// into the order and units the kernels read.  No device work happens here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+#include "sconv_internal.h"
+
+namespace sconv {
+
+int validate_desc(const sconv_desc &d)
+{
+    if (d.C < 1 || d.H < 1 || d.W < 1 || d.K < 1 || d.R < 1 || d.S < 1) return SCONV_ERR_DESC;
+    if (d.stride < 1 || d.pad < 0 || d.groups < 1) return SCONV_ERR_DESC;
+    if (d.C % d.groups || d.K % d.groups) return SCONV_ERR_DESC;
+    if ((int64_t)d.H + 2 * (int64_t)d.pad < d.R || (int64_t)d.W + 2 * (int64_t)d.pad < d.S) return SCONV_ERR_DESC;
+    // offsets inside one (padded) image and one group's CSR columns must fit int32
+    const int64_t Hp = (int64_t)d.H + 2 * d.pad, Wp = (int64_t)d.W + 2 * d.pad;
+    if ((int64_t)d.C * Hp * Wp >= (int64_t)1 << 30) return SCONV_ERR_RANGE;
+    if ((int64_t)(d.C / d.groups) * d.R * d.S >= (int64_t)1 << 30) return SCONV_ERR_RANGE;
+    if ((int64_t)d.K * (d.C / d.groups) * d.R * d.S >= (int64_t)1 << 31) return SCONV_ERR_RANGE;
+    if (d.R > 255 || d.S > 255 || d.pad > 255) return SCONV_ERR_RANGE;
+    return SCONV_OK;
+}
+
+// Figure 2's layout function on the zero-padded CHW image: f(c,r,s) = (c*Hp + r)*Wp + s.
+static void lower(const sconv_desc &d, Canonical &c)
+{
+    const Geometry g = geometry(d);
+    const int nnz = (int)c.colidx.size();
+    c.off.resize(nnz);
+    for (int k = 0; k < d.K; ++k) {
+        const int grp = k / g.Kg;
+        for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
+            const int col = c.colidx[j];
+            const int s = col % d.S, r = (col / d.S) % d.R, ch = col / (d.S * d.R);
+            c.off[j] = ((grp * g.Cg + ch) * g.Hp + r) * g.Wp + s;
+        }
+    }
+}
+
+int build_canonical_from_dense(const sconv_desc &d, const float *w, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    const int64_t ncol = (int64_t)g.Cg * d.R * d.S;
+    out.rowptr.assign(d.K + 1, 0);
+    out.colidx.clear();
+    out.val.clear();
+    for (int k = 0; k < d.K; ++k) {
+        const float *row = w + (int64_t)k * ncol;
+        for (int64_t j = 0; j < ncol; ++j) {
+            if (row[j] == 0.0f) continue; // +0 and -0 are pruned; NaN compares unequal and stays
+            out.colidx.push_back((int32_t)j);
+            out.val.push_back(row[j]);
+        }
+        out.rowptr[k + 1] = (int32_t)out.colidx.size();
+    }
+    lower(d, out);
+    return SCONV_OK;
+}
+
+int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx,
+                                const float *values, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    const int64_t ncol = (int64_t)g.Cg * d.R * d.S;
+    if (rowptr[0] != 0) return SCONV_ERR_CSR;
+    for (int k = 0; k < d.K; ++k)
+        if (rowptr[k + 1] < rowptr[k]) return SCONV_ERR_CSR;
+    const int32_t nnz = rowptr[d.K];
+    if (nnz > 0 && (!colidx || !values)) return SCONV_ERR_NULL;
+    for (int k = 0; k < d.K; ++k) {
+        if ((int64_t)rowptr[k + 1] - rowptr[k] > ncol) return SCONV_ERR_CSR;
+        for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
+            if (colidx[j] < 0 || colidx[j] >= ncol) return SCONV_ERR_CSR;
+            if (j > rowptr[k] && colidx[j] <= colidx[j - 1]) return SCONV_ERR_CSR;
+        }
+    }
+    out.rowptr.assign(rowptr, rowptr + d.K + 1);
+    out.colidx.assign(colidx, colidx + nnz);
+    out.val.assign(values, values + nnz);
+    lower(d, out);
+    return SCONV_OK;
+}
+
+// ------------------------------------------------------------------ tiling
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Row pitch of the LDS plane.  W + pad columns are enough for the reads: one that runs into the right
+// padding of a row (X >= W + pad) lands on column X - pitch < pad of the next row, left padding, zero as
+// well.  The pitch must also hold a whole output row, which is wider than that when pad > S - 1.
+static int lds_pitch(const sconv_desc &d)
+{
+    const Geometry g = geometry(d);
+    return std::max(d.W + d.pad, g.OW);
+}
+
+static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
+{
+    const Geometry g = geometry(d);
+    if (d.stride != 1) return SCONV_ERR_PLAN;
+    if (p.nt < 1 || p.cb < 1 || p.waves < 1 || p.waves > 16 || p.cg < 1 || p.rows_w < 1 || p.t < 1) return SCONV_ERR_PLAN;
+    if (p.waves % p.cg) return SCONV_ERR_PLAN;
+    t.p = p;
+    t.p.kernel = 1;
+    t.vec = (p.nt % 4 == 0) ? 4 : 1;
+    if ((64 * t.vec) % p.nt) return SCONV_ERR_PLAN;
+    if (!lds_kernel_available(t.vec, p.t, p.rows_w)) return SCONV_ERR_PLAN;
+    t.Wl = lds_pitch(d);
+    t.Hl = g.Hp;
+    t.plane_cells = t.Hl * t.Wl;
+    t.pos_span = (g.OH - 1) * t.Wl + g.OW;
+    t.pos_per_chunk = 64 * t.vec / p.nt;
+    t.n_chunks = ceil_div(t.pos_span, t.pos_per_chunk);
+    if (t.n_chunks > p.cg * p.t) return SCONV_ERR_PLAN;
+    if (p.cb > g.Cg) t.p.cb = g.Cg;
+    t.nblk = ceil_div(g.Cg, t.p.cb);
+    t.rg = p.waves / p.cg;
+    const int kt = t.rg * p.rows_w;
+    t.nkt = ceil_div(g.Kg, kt);
+    t.wave_slots = d.groups * t.nkt * t.rg;
+    t.items = t.plane_cells * p.nt / t.vec;
+    const int threads = p.waves * 64;
+    int grp = 64;
+    while (grp < t.items && grp < threads) grp *= 2;
+    if (grp > threads) grp = threads; // waves not a power of two: fall back to the whole workgroup
+    if (threads % grp) grp = 64;
+    t.stage_group = grp;
+    if (ceil_div(t.items, grp) > 4) return SCONV_ERR_PLAN; // items one thread stages per channel
+    // LDS layout in floats: [staged block: cb*plane_cells*nt][zero page: cg*t*64*vec].  The zero page is
+    // cleared once per launch and never written.  It serves three readers: the right padding of the very
+    // last row (pad*nt floats past the block), lanes past the last valid position (their results are
+    // dropped), and the padding entries of the nonzero stream, whose offset is the page's start, so that
+    // they multiply 0 by 0 for every lane and chunk.
+    const int64_t staged = (int64_t)t.p.cb * t.plane_cells * p.nt;
+    const int64_t page = (int64_t)p.cg * p.t * 64 * t.vec;
+    if (page < (int64_t)d.pad * p.nt) return SCONV_ERR_PLAN;
+    int64_t floats = staged + page;
+    floats = (floats + 3) / 4 * 4;
+    if (floats * 4 > 160 * 1024) return SCONV_ERR_PLAN;
+    t.lds_bytes = (int)(floats * 4);
+    t.staged_floats = (int)staged;
+    t.zero_page = (unsigned)(staged * 4);
+    // byte offsets (value pairs) and per-wave chunk offsets must stay below 2^31; trivially true here.
+    return SCONV_OK;
+}
+
+// Supported accumulator shapes; must match the instantiations in sconv_kernels.hip.
+static const int kShapesV4[][2] = {{1, 8}, {2, 4}, {2, 8}, {3, 4}, {3, 6}, {3, 8}, {4, 4}, {4, 6}, {5, 4},
+                                   {6, 2}, {6, 3}, {7, 2}, {7, 3}, {13, 1}, {14, 1}};
+static const int kShapesV1[][2] = {{1, 16}, {2, 16}, {3, 8}, {3, 16}, {4, 8}, {7, 8}, {13, 4}, {14, 4}};
+
+bool lds_kernel_available(int vec, int t, int rows_w)
+{
+    if (vec == 4) {
+        for (auto &s : kShapesV4)
+            if (s[0] == t && s[1] == rows_w) return true;
+    } else if (vec == 1) {
+        for (auto &s : kShapesV1)
+            if (s[0] == t && s[1] == rows_w) return true;
+    }
+    return false;
+}
+
+// Rough cost of a tiling in CU clocks; only used to rank candidates.
+static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double avg_row_nnz)
+{
+    const Geometry g = geometry(d);
+    const int n_tiles = ceil_div(N, t.p.nt);
+    const double wgs = (double)n_tiles * d.groups * t.nkt;
+    const int by_lds = std::max(1, (160 * 1024) / (t.lds_bytes + 512));
+    const int by_waves = std::max(1, 16 / t.p.waves);
+    const int wpc = std::min(by_lds, by_waves);
+    const double rows_per_wave = (double)g.Kg / (t.nkt * t.rg); // after dealing rows evenly
+    const double nnz_wave = rows_per_wave * avg_row_nnz;
+    const double fma_instr = t.p.t * t.vec;
+    // SIMD-issue bound: waves on a SIMD run one after another; 4 clocks per wave instruction.
+    const double simd = std::ceil(t.p.waves / 4.0) * nnz_wave * 4.0 * (fma_instr + 2.0);
+    // LDS bound: clocks per wave read instruction.
+    const double lds = t.p.waves * nnz_wave * t.p.t * (t.vec == 4 ? 4.3 : 2.4);
+    // per segment fixed costs (pointer fetch, loop set-up, scalar latency), per wave, partly hidden
+    const double seg = (double)t.nblk * t.p.rows_w * 60.0 * std::ceil(t.p.waves / 4.0);
+    const double stage = (double)g.Cg * t.plane_cells * t.p.nt * 4.0 / 48.0 + t.nblk * 1500.0;
+    const double wg = std::max(simd, lds) + seg + stage / wpc;
+    const double rounds = std::ceil(wgs / (256.0 * wpc));
+    return rounds * wpc * wg;
+}
+
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
+{
+    const Geometry g = geometry(d);
+    if (d.stride != 1) return SCONV_ERR_PLAN;
+    const bool full = req.nt && req.cb && req.waves && req.cg && req.rows_w && req.t;
+    if (full) return fill_tiling(d, req, out);
+
+    double best = -1;
+    const int nts_big[] = {4, 8, 16};
+    const int nts_small[] = {1, 2};
+    const int *nts = N_hint >= 4 ? nts_big : nts_small;
+    const int n_nts = N_hint >= 4 ? 3 : 2;
+    for (int a = 0; a < n_nts; ++a) {
+        const int nt = nts[a];
+        if (req.nt && req.nt != nt) continue;
+        if (nt > 1 && nt > N_hint) continue;
+        const int vec = nt % 4 == 0 ? 4 : 1;
+        const int Wl = lds_pitch(d);
+        const int pos_span = (g.OH - 1) * Wl + g.OW;
+        const int n_chunks = ceil_div(pos_span, 64 * vec / nt);
+        for (int waves : {4, 8, 16}) {
+            if (req.waves && req.waves != waves) continue;
+            for (int cg = 1; cg <= 4; ++cg) {
+                if (waves % cg) continue;
+                if (req.cg && req.cg != cg) continue;
+                const int T = ceil_div(n_chunks, cg);
+                if (req.t && req.t != T) continue;
+                const int (*shapes)[2] = vec == 4 ? kShapesV4 : kShapesV1;
+                const int n_shapes = vec == 4 ? (int)(sizeof(kShapesV4) / sizeof(kShapesV4[0]))
+                                              : (int)(sizeof(kShapesV1) / sizeof(kShapesV1[0]));
+                for (int si = 0; si < n_shapes; ++si) {
+                    if (shapes[si][0] != T) continue;
+                    const int rows_w = shapes[si][1];
+                    if (req.rows_w && req.rows_w != rows_w) continue;
+                    for (int wpc_target : {1, 2, 4}) {
+                        if (waves * wpc_target > 16) continue;
+                        const int budget = 160 * 1024 / wpc_target - 1024;
+                        const int64_t per_ch = (int64_t)g.Hp * Wl * nt * 4;
+                        const int64_t fixed = (int64_t)cg * T * 64 * vec * 4 + 16;
+                        int cb = (int)std::min<int64_t>(g.Cg, (budget - fixed) / per_ch + 0);
+                        if (req.cb) cb = req.cb;
+                        if (cb < 1) continue;
+                        // even out the blocks
+                        if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
+                        sconv_plan p = {1, nt, cb, waves, cg, rows_w, T};
+                        LdsTiling t;
+                        if (fill_tiling(d, p, t) != SCONV_OK) continue;
+                        const double c = tiling_cost(d, t, N_hint, avg_row_nnz);
+                        if (best < 0 || c < best) {
+                            best = c;
+                            out = t;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return best < 0 ? SCONV_ERR_PLAN : SCONV_OK;
+}
+
+// ------------------------------------------------------------------ packing
+
+// Rows of one group are dealt to the group's wave slots in descending order of their nonzero count,
+// boustrophedon, so that every wave (which owns rows_w rows for the whole kernel) gets about the same
+// number of nonzeros even when the row lengths are skewed; empty rows are dealt like any other row
+// and simply produce empty segments.
+int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedLds &out)
+{
+    const Geometry g = geometry(d);
+    const int rows_w = t.p.rows_w, cb = t.p.cb, nt = t.p.nt;
+    const int waves_per_group = t.nkt * t.rg;
+    out.t = t;
+    out.row_of.assign((size_t)t.wave_slots * rows_w, -1);
+    for (int grp = 0; grp < d.groups; ++grp) {
+        std::vector<int> rows(g.Kg);
+        std::iota(rows.begin(), rows.end(), grp * g.Kg);
+        std::stable_sort(rows.begin(), rows.end(), [&](int a, int b) {
+            return c.rowptr[a + 1] - c.rowptr[a] > c.rowptr[b + 1] - c.rowptr[b];
+        });
+        for (int i = 0; i < g.Kg; ++i) {
+            const int round = i / waves_per_group, posn = i % waves_per_group;
+            const int w = (round & 1) ? waves_per_group - 1 - posn : posn;
+            if (round >= rows_w) return SCONV_ERR_PLAN; // cannot happen: nkt*rg*rows_w >= Kg
+            out.row_of[((size_t)grp * waves_per_group + w) * rows_w + round] = rows[i];
+        }
+    }
+    out.seg_ptr.assign((size_t)t.wave_slots * t.nblk * (rows_w + 1), 0);
+    out.pairs.clear();
+    out.pairs.reserve(c.val.size() + c.val.size() / 4);
+    size_t real = 0;
+    for (int ws = 0; ws < t.wave_slots; ++ws) {
+        for (int b = 0; b < t.nblk; ++b) {
+            int32_t *sp = &out.seg_ptr[((size_t)ws * t.nblk + b) * (rows_w + 1)];
+            for (int i = 0; i < rows_w; ++i) {
+                sp[i] = (int32_t)out.pairs.size();
+                const int k = out.row_of[(size_t)ws * rows_w + i];
+                if (k < 0) continue;
+                const int grp = k / g.Kg;
+                for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
+                    // canonical offset -> (absolute channel, r, s)
+                    const int off = c.off[j];
+                    const int s = off % g.Wp, r = (off / g.Wp) % g.Hp, ca = off / (g.Wp * g.Hp);
+                    const int cl = ca - grp * g.Cg - b * cb;
+                    if (cl < 0 || cl >= cb) continue;
+                    const uint32_t byte_off = (uint32_t)(((int64_t)cl * t.plane_cells + r * t.Wl + s) * nt * 4);
+                    uint32_t vb;
+                    std::memcpy(&vb, &c.val[j], 4);
+                    out.pairs.push_back((uint64_t)vb | ((uint64_t)byte_off << 32));
+                    ++real;
+                }
+                // pad the segment to whole groups: value +0.0 at the all-zero page
+                while ((out.pairs.size() - (size_t)sp[i]) % SCONV_PAIR_GROUP) out.pairs.push_back((uint64_t)t.zero_page << 32);
+            }
+            sp[rows_w] = (int32_t)out.pairs.size();
+        }
+    }
+    if (real != c.val.size()) return SCONV_ERR_PLAN;
+    // the kernel prefetches up to three chunks past the stream it is working on
+    for (int i = 0; i < 3 * SCONV_PAIR_GROUP; ++i) out.pairs.push_back((uint64_t)t.zero_page << 32);
+    return SCONV_OK;
+}
+
+static void sort_rows_by_offset(const sconv_desc &d, std::vector<std::vector<std::pair<int32_t, float>>> &rows,
+                                Canonical &out)
+{
+    out.rowptr.assign(d.K + 1, 0);
+    out.off.clear();
+    out.val.clear();
+    out.colidx.clear();
+    for (int k = 0; k < d.K; ++k) {
+        auto &r = rows[k];
+        std::stable_sort(r.begin(), r.end(), [](const std::pair<int32_t, float> &a, const std::pair<int32_t, float> &b) {
+            return a.first < b.first;
+        });
+        for (auto &e : r) {
+            out.off.push_back(e.first);
+            out.val.push_back(e.second);
+        }
+        out.rowptr[k + 1] = (int32_t)out.off.size();
+    }
+}
+
+int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    const LdsTiling &t = p.t;
+    const int rows_w = t.p.rows_w;
+    std::vector<std::vector<std::pair<int32_t, float>>> rows(d.K);
+    for (int ws = 0; ws < t.wave_slots; ++ws) {
+        for (int b = 0; b < t.nblk; ++b) {
+            const int32_t *sp = &p.seg_ptr[((size_t)ws * t.nblk + b) * (rows_w + 1)];
+            for (int i = 0; i < rows_w; ++i) {
+                const int k = p.row_of[(size_t)ws * rows_w + i];
+                if (k < 0) {
+                    if (sp[i + 1] != sp[i]) return SCONV_ERR_CSR;
+                    continue;
+                }
+                const int grp = k / g.Kg;
+                for (int j = sp[i]; j < sp[i + 1]; ++j) {
+                    const uint32_t vb = (uint32_t)(p.pairs[j] & 0xffffffffu);
+                    const uint32_t byte_off = (uint32_t)(p.pairs[j] >> 32);
+                    if (byte_off >= t.zero_page) continue; // group padding
+                    const int cell = (int)(byte_off / (4u * t.p.nt));
+                    const int cl = cell / t.plane_cells, rem = cell % t.plane_cells;
+                    const int r = rem / t.Wl, s = rem % t.Wl;
+                    const int ca = grp * g.Cg + b * t.p.cb + cl;
+                    float v;
+                    std::memcpy(&v, &vb, 4);
+                    rows[k].push_back({((ca * g.Hp) + r) * g.Wp + s, v});
+                }
+            }
+        }
+    }
+    sort_rows_by_offset(d, rows, out);
+    return SCONV_OK;
+}
+
+// Direct kernel: per nonzero the value, the offset of (c, r-pad, s-pad) in the UNPADDED image
+// (may be negative), and (r-pad, s-pad) for the bounds test that stands in for the zero padding.
+int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out)
+{
+    const Geometry g = geometry(d);
+    out.rowptr = c.rowptr;
+    out.trip.resize(c.val.size() * 3);
+    for (size_t j = 0; j < c.val.size(); ++j) {
+        const int off = c.off[j];
+        const int s = off % g.Wp, r = (off / g.Wp) % g.Hp, ca = off / (g.Wp * g.Hp);
+        const int dr = r - d.pad, ds = s - d.pad;
+        const int32_t goff = (ca * d.H + dr) * d.W + ds;
+        uint32_t vb;
+        std::memcpy(&vb, &c.val[j], 4);
+        out.trip[3 * j + 0] = vb;
+        out.trip[3 * j + 1] = (uint32_t)goff;
+        out.trip[3 * j + 2] = ((uint32_t)(dr & 0xffff) << 16) | (uint32_t)(ds & 0xffff);
+    }
+    return SCONV_OK;
+}
+
+int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    std::vector<std::vector<std::pair<int32_t, float>>> rows(d.K);
+    for (int k = 0; k < d.K; ++k) {
+        for (int j = p.rowptr[k]; j < p.rowptr[k + 1]; ++j) {
+            const uint32_t vb = p.trip[3 * (size_t)j];
+            const int32_t goff = (int32_t)p.trip[3 * (size_t)j + 1];
+            const uint32_t rs = p.trip[3 * (size_t)j + 2];
+            const int dr = (int16_t)(rs >> 16), ds = (int16_t)(rs & 0xffff);
+            const int ca = (goff - dr * d.W - ds) / (d.H * d.W);
+            float v;
+            std::memcpy(&v, &vb, 4);
+            rows[k].push_back({((ca * g.Hp) + dr + d.pad) * g.Wp + ds + d.pad, v});
+        }
+    }
+    sort_rows_by_offset(d, rows, out);
+    return SCONV_OK;
+}
+
+} // namespace sconv

@@ -1,0 +1,107 @@
+// Internal declarations shared by the host code and the kernel launchers of libsconv.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "sconv.h"
+
+namespace sconv {
+
+// Nonzeros per straight-line group of the LDS kernel; (row, block) segments are padded to a multiple.
+#define SCONV_PAIR_GROUP 4
+
+struct Geometry {
+    int Cg, Kg, Hp, Wp, OH, OW;
+};
+
+inline Geometry geometry(const sconv_desc &d)
+{
+    Geometry g;
+    g.Cg = d.C / d.groups;
+    g.Kg = d.K / d.groups;
+    g.Hp = d.H + 2 * d.pad;
+    g.Wp = d.W + 2 * d.pad;
+    g.OH = (g.Hp - d.R) / d.stride + 1;
+    g.OW = (g.Wp - d.S) / d.stride + 1;
+    return g;
+}
+
+// Tiling of the LDS kernel, derived from a sconv_plan and the layer.
+//
+// LDS holds one block of `cb` input channels of `nt` images as
+// [channel][cell][image]: `cell` runs over a Hl x Wl plane of the zero-padded
+// image, `image` is innermost so that a lane reading `vec` consecutive floats
+// reads `vec` images at one cell, always at an aligned address.  The row pitch
+// is Wl = max(W + pad, OW): a read that falls into the right padding of a row
+// lands on the left padding of the next one, which is zero as well.
+// A nonzero (c,r,s) of a row then reads, for flat output index
+// F = pos*nt + image with pos = y*Wl + x, the float at
+//   ((c_local*plane_cells + r*Wl + s)*nt) + F,
+// i.e. the packed byte offset plus a per-lane constant.
+struct LdsTiling {
+    sconv_plan p;
+    int vec;            // floats per lane per chunk: 4 if nt % 4 == 0 else 1
+    int Wl, Hl;         // plane pitch and rows
+    int plane_cells;    // Hl * Wl
+    int pos_span;       // (OH-1)*Wl + OW: positions a tile computes
+    int pos_per_chunk;  // 64*vec / nt
+    int n_chunks;       // ceil(pos_span / pos_per_chunk), <= cg*t
+    int nblk;           // ceil(Cg / cb)
+    int rg;             // row groups = waves / cg
+    int nkt;            // K tiles per group
+    int wave_slots;     // groups * nkt * rg
+    int items;          // staging items per channel: plane_cells * nt / vec
+    int stage_group;    // threads that cooperate on one channel (power of two)
+    int lds_bytes;      // dynamic LDS per workgroup
+    int staged_floats;  // cb * plane_cells * nt: what staging writes; everything after it stays zero
+    unsigned zero_page; // byte offset of a region that is zero for every lane and chunk (padding entries)
+};
+
+struct PackedLds {
+    LdsTiling t;
+    std::vector<uint64_t> pairs;   // low 32 bits: fp32 value bits; high 32: LDS byte offset
+    std::vector<int32_t> seg_ptr;  // [wave_slot][nblk][rows_w + 1] -> index into pairs
+    std::vector<int32_t> row_of;   // [wave_slot][rows_w] -> output channel or -1
+};
+
+struct PackedDirect {
+    std::vector<int32_t> rowptr;   // K+1
+    std::vector<uint32_t> trip;    // 3 words per nonzero: value bits, goff, (dr<<16)|(ds&0xffff)
+};
+
+struct Canonical {
+    std::vector<int32_t> rowptr, colidx, off;
+    std::vector<float> val;
+};
+
+int validate_desc(const sconv_desc &d);
+int build_canonical_from_dense(const sconv_desc &d, const float *w, Canonical &out);
+int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx,
+                                const float *values, Canonical &out);
+
+// Fill in a tiling for the LDS kernel (fields of `req` that are 0 are chosen).  N_hint is the
+// batch size the choice is tuned for.  Returns SCONV_ERR_PLAN if the layer cannot use it.
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out);
+bool lds_kernel_available(int vec, int t, int rows_w);
+
+int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedLds &out);
+int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out);
+int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
+int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
+
+// Device side (sconv_kernels.hip)
+struct DeviceLds {
+    void *pairs = nullptr, *seg_ptr = nullptr, *row_of = nullptr;
+};
+struct DeviceDirect {
+    void *rowptr = nullptr, *trip = nullptr;
+};
+int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
+               int N, void *stream, int *hip_err);
+int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
+                  void *stream, int *hip_err);
+int upload(const void *host, size_t bytes, void **dev, int *hip_err);
+void release(void *dev);
+
+} // namespace sconv

@@ -1,0 +1,339 @@
+// HIP kernels for direct sparse convolution on gfx950 and their launchers.
+//
+// sconv_lds_kernel: the hot path for stride-1 layers (Section 2.1's loop nest with the input and
+// output channels tiled and the weight matrix column-blocked, re-thought for CDNA4):
+//   * a workgroup owns `nt` images and a tile of CSR rows (output channels) and walks the input
+//     channels of its group in blocks of `cb`;
+//   * each block is staged global -> LDS as [channel][cell][image], zero padding included; the image
+//     index is innermost so that a lane's read of 4 images at one cell is one aligned ds_read_b128
+//     whatever the nonzero's offset is;
+//   * the nonzeros (value, LDS byte offset) of a wave's rows are wave-uniform: they come through
+//     scalar loads and sit in SGPRs; lanes span (output position, image);
+//   * accumulators stay in VGPRs across all channel blocks and are stored once.
+// sconv_direct_kernel: any stride, small batches; reads the unpadded input straight from global
+// memory with a bounds test standing in for the padding.
+#include <hip/hip_runtime.h>
+
+#include "sconv_internal.h"
+
+namespace sconv {
+
+struct LdsArgs {
+    const float *in;
+    float *out;
+    const unsigned *pairs; // (value bits, LDS byte offset) per nonzero
+    const int *seg_ptr;
+    const int *row_of;
+    int N, C, H, W, K, OH, OW, pad, Cg, groups;
+    int nt, cb, nblk, rg, cg, nkt;
+    int Wl, plane_cells, items, stage_group_log2, lds_floats, staged_floats;
+    int n_tiles, units;
+};
+
+constexpr int kMaxItemsPerThread = 4;
+constexpr int kGroup = SCONV_PAIR_GROUP; // nonzeros per straight-line group; segments are padded to it
+using const_u32 = const __attribute__((address_space(4))) unsigned;
+
+#include "sconv_lds_loops.inc"
+
+template <int VEC>
+struct VecT;
+template <>
+struct VecT<4> {
+    using type = float4;
+};
+template <>
+struct VecT<1> {
+    using type = float;
+};
+
+template <int VEC, int T, int ROWS_W>
+__global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
+{
+    using vec_t = typename VecT<VEC>::type;
+    extern __shared__ float4 smem4[];
+    float *lds = reinterpret_cast<float *>(smem4);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // Consecutive workgroup ids land on different XCDs (each with its own L2); the workgroups that
+    // share one image tile (same input, different rows) are given ids 8 apart so they meet in one L2.
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int unit = slot % a.units;
+    const int tile = (slot / a.units) * 8 + xcd;
+    if (tile >= a.n_tiles) return;
+    const int g = unit / a.nkt, kt = unit - g * a.nkt;
+    const int n0 = tile * a.nt;
+    const int rgi = __builtin_amdgcn_readfirstlane(wave / a.cg);
+    const int cgi = wave - rgi * a.cg;
+    const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
+
+    const int HW = a.H * a.W;
+    const int CHW = a.C * HW;
+    const float *in_tile = a.in + (size_t)n0 * CHW;
+
+    // ---- staging set-up: this thread always handles the same cells, for every channel and block.
+    const int G = 1 << a.stage_group_log2;
+    const int tg = tid & (G - 1);
+    const int csub = tid >> a.stage_group_log2;
+    const int n_par = (int)blockDim.x >> a.stage_group_log2;
+    const int q_cnt = a.nt / VEC;
+    int src_off[kMaxItemsPerThread]; // offset of (first image of the lane, channel 0, iy, ix) in the tile, -1: padding, -2: no item
+    int img0[kMaxItemsPerThread];
+#pragma unroll
+    for (int ii = 0; ii < kMaxItemsPerThread; ++ii) {
+        const int item = tg + ii * G;
+        src_off[ii] = -2;
+        img0[ii] = 0;
+        if (item < a.items) {
+            const int cell = item / q_cnt, q = item - cell * q_cnt;
+            const int Y = cell / a.Wl, X = cell - Y * a.Wl;
+            const int iy = Y - a.pad, ix = X - a.pad;
+            const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+            img0[ii] = q * VEC;
+            src_off[ii] = inside ? q * VEC * CHW + iy * a.W + ix : -1;
+        }
+    }
+    for (int i = a.staged_floats + tid; i < a.lds_floats; i += blockDim.x) lds[i] = 0.f;
+
+    // acc[(i*T + t)*VEC + e]: row i of this wave, chunk t, image e of the lane's quad
+    float acc[ROWS_W * T * VEC];
+#pragma unroll
+    for (int i = 0; i < ROWS_W * T * VEC; ++i) acc[i] = 0.f;
+
+    const unsigned lane_byte = (unsigned)((cgi * T * 64 + lane) * VEC * 4);
+    const char *lds_bytes = reinterpret_cast<const char *>(lds);
+    // the nonzero stream is read-only for the whole launch: constant address space => scalar loads
+    const_u32 *cp = (const_u32 *)(a.pairs);
+    const_u32 *cseg = (const_u32 *)(a.seg_ptr);
+    const_u32 *crow = (const_u32 *)(a.row_of);
+
+    for (int b = 0; b < a.nblk; ++b) {
+        const int c0 = g * a.Cg + b * a.cb;
+        const int cb_here = min(a.cb, a.Cg - b * a.cb);
+        if (b > 0) __syncthreads();
+        for (int cl = csub; cl < cb_here; cl += n_par) {
+            // uniform part of the address (image e of the lane's quad, channel) stays in SGPRs
+            const float *chan = in_tile + (size_t)(c0 + cl) * HW;
+#pragma unroll
+            for (int ii = 0; ii < kMaxItemsPerThread; ++ii) {
+                if (src_off[ii] == -2) continue;
+                float v[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const bool ok = src_off[ii] >= 0 && n0 + img0[ii] + e < a.N;
+                    const float *pe = chan + (size_t)e * CHW;
+                    v[e] = ok ? pe[src_off[ii]] : 0.f;
+                }
+                const int item = tg + ii * G;
+                vec_t *dst = reinterpret_cast<vec_t *>(lds) + (cl * a.items + item);
+                if constexpr (VEC == 4)
+                    *dst = make_float4(v[0], v[1], v[2], v[3]);
+                else
+                    *dst = v[0];
+            }
+        }
+        __syncthreads();
+
+        // Nonzeros of this wave's rows inside this channel block.  Every (row, block) segment is padded
+        // on the host to whole chunks of kGroup entries (padding: value 0 at an all-zero LDS page).
+        const_u32 *sp = cseg + ((size_t)wslot * a.nblk + b) * (ROWS_W + 1);
+        int ptr[ROWS_W + 1];
+#pragma unroll
+        for (int i = 0; i <= ROWS_W; ++i) ptr[i] = (int)sp[i];
+        if constexpr (VEC == 4) {
+            int cnt[ROWS_W];
+#pragma unroll
+            for (int i = 0; i < ROWS_W; ++i) cnt[i] = (ptr[i + 1] - ptr[i]) / kGroup;
+            if (ptr[ROWS_W] > ptr[0]) SegLoop<T, ROWS_W>::run(acc, a.pairs + 2 * (size_t)ptr[0], cnt, lane_byte);
+        } else {
+#pragma unroll
+            for (int i = 0; i < ROWS_W; ++i) {
+                for (int j = ptr[i]; j < ptr[i + 1]; ++j) {
+                    const float w = __uint_as_float(cp[2 * j]);
+                    const float *src = reinterpret_cast<const float *>(lds_bytes + (lane_byte + cp[2 * j + 1]));
+#pragma unroll
+                    for (int t = 0; t < T; ++t) acc[i * T + t] = fmaf(w, src[t * 64], acc[i * T + t]);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: flat index F = pos*nt + image; a lane's VEC floats are VEC images at one position.
+    const int OHW = a.OH * a.OW;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int F0 = ((cgi * T + t) * 64 + lane) * VEC;
+        const int pos = F0 / a.nt, nl = F0 - pos * a.nt;
+        const int oy = pos / a.Wl, ox = pos - oy * a.Wl;
+        const bool valid = ox < a.OW && oy < a.OH;
+#pragma unroll
+        for (int i = 0; i < ROWS_W; ++i) {
+            const int k = (int)crow[wslot * ROWS_W + i];
+            if (k < 0) continue;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int n = n0 + nl + e;
+                if (valid && n < a.N) a.out[((size_t)n * a.K + k) * OHW + oy * a.OW + ox] = acc[(i * T + t) * VEC + e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+
+struct DirectArgs {
+    const float *in;
+    float *out;
+    const int *rowptr;
+    const uint32_t *trip;
+    int N, C, H, W, K, OH, OW, stride, pad;
+};
+
+__global__ void __launch_bounds__(256) sconv_direct_kernel(const DirectArgs a)
+{
+    const int k = blockIdx.y;
+    const int OHW = a.OH * a.OW;
+    const long long total = (long long)a.N * OHW;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    const bool live = idx < total;
+    const long long idc = live ? idx : total - 1;
+    const int n = (int)(idc / OHW);
+    const int rem = (int)(idc - (long long)n * OHW);
+    const int oy = rem / a.OW, ox = rem - oy * a.OW;
+    const int y0 = oy * a.stride, x0 = ox * a.stride;
+    const float *src = a.in + (size_t)n * a.C * a.H * a.W + y0 * a.W + x0;
+    float acc = 0.f;
+    const int j0 = a.rowptr[k], j1 = a.rowptr[k + 1];
+    for (int j = j0; j < j1; ++j) {
+        const float w = __uint_as_float(a.trip[3 * (size_t)j]);
+        const int goff = (int)a.trip[3 * (size_t)j + 1];
+        const uint32_t rs = a.trip[3 * (size_t)j + 2];
+        const int dr = (int)(short)(rs >> 16), ds = (int)(short)(rs & 0xffffu);
+        const int iy = y0 + dr, ix = x0 + ds;
+        const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+        const float v = inside ? src[goff] : 0.f;
+        acc = fmaf(w, v, acc);
+    }
+    if (live) a.out[((size_t)n * a.K + k) * OHW + rem] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+
+int upload(const void *host, size_t bytes, void **dev, int *hip_err)
+{
+    *dev = nullptr;
+    if (bytes == 0) bytes = 16; // keep a valid pointer for empty patterns
+    hipError_t e = hipMalloc(dev, bytes);
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    if (host) {
+        e = hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            *hip_err = (int)e;
+            (void)hipFree(*dev);
+            *dev = nullptr;
+            return SCONV_ERR_HIP;
+        }
+    }
+    return SCONV_OK;
+}
+
+void release(void *dev)
+{
+    if (dev) (void)hipFree(dev);
+}
+
+template <int VEC, int T, int ROWS_W>
+static int launch_lds_inst(const LdsArgs &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
+{
+    auto kern = sconv_lds_kernel<VEC, T, ROWS_W>;
+    static int max_set = 0; // largest dynamic LDS size this instantiation has been enabled for
+    if (lds_bytes > max_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) {
+            *hip_err = (int)e;
+            return SCONV_ERR_HIP;
+        }
+        max_set = 160 * 1024;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+#define SCONV_SHAPES_V1(X) \
+    X(1, 1, 16) X(1, 2, 16) X(1, 3, 8) X(1, 3, 16) X(1, 4, 8) X(1, 7, 8) X(1, 13, 4) X(1, 14, 4)
+
+int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
+               int N, void *stream, int *hip_err)
+{
+    const Geometry g = geometry(d);
+    LdsArgs a;
+    a.in = in;
+    a.out = out;
+    a.pairs = static_cast<const unsigned *>(dev.pairs);
+    a.seg_ptr = static_cast<const int *>(dev.seg_ptr);
+    a.row_of = static_cast<const int *>(dev.row_of);
+    a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.pad = d.pad;
+    a.Cg = g.Cg; a.groups = d.groups;
+    a.nt = t.p.nt; a.cb = t.p.cb; a.nblk = t.nblk; a.rg = t.rg; a.cg = t.p.cg; a.nkt = t.nkt;
+    a.Wl = t.Wl; a.plane_cells = t.plane_cells; a.items = t.items;
+    int lg = 0;
+    while ((1 << lg) < t.stage_group) ++lg;
+    a.stage_group_log2 = lg;
+    a.lds_floats = t.lds_bytes / 4;
+    a.staged_floats = t.staged_floats;
+    a.n_tiles = (N + t.p.nt - 1) / t.p.nt;
+    a.units = d.groups * t.nkt;
+    // the kernel's own assumptions, checked before anything is launched
+    if ((1 << lg) != t.stage_group || (t.items + t.stage_group - 1) / t.stage_group > kMaxItemsPerThread) return SCONV_ERR_PLAN;
+    if ((int64_t)t.p.nt * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;
+    if (a.staged_floats > a.lds_floats) return SCONV_ERR_PLAN;
+    const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
+    if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
+    const int grid = (int)grid64, threads = t.p.waves * 64;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define X(V, TT, RW) \
+    if (t.vec == V && t.p.t == TT && t.p.rows_w == RW) return launch_lds_inst<V, TT, RW>(a, grid, threads, t.lds_bytes, s, hip_err);
+    SCONV_SHAPES_V1(X)
+#undef X
+#define X(TT, RW) \
+    if (t.vec == 4 && t.p.t == TT && t.p.rows_w == RW) return launch_lds_inst<4, TT, RW>(a, grid, threads, t.lds_bytes, s, hip_err);
+    SCONV_ASM_SHAPES(X)
+#undef X
+    return SCONV_ERR_PLAN;
+}
+
+int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
+                  void *stream, int *hip_err)
+{
+    const Geometry g = geometry(d);
+    DirectArgs a;
+    a.in = in;
+    a.out = out;
+    a.rowptr = static_cast<const int *>(dev.rowptr);
+    a.trip = static_cast<const uint32_t *>(dev.trip);
+    a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.stride = d.stride; a.pad = d.pad;
+    const int64_t total = (int64_t)N * g.OH * g.OW;
+    const int64_t gx = (total + 255) / 256;
+    if (gx > 0x7fffffff || d.K > 65535) return SCONV_ERR_RANGE;
+    hipLaunchKernelGGL(sconv_direct_kernel, dim3((unsigned)gx, (unsigned)d.K), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+} // namespace sconv

@@ -1,0 +1,202 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs, element by element.
+
+Tolerance (fp32 accumulation on the GPU against the oracle's fp64 sum):
+|gpu - oracle| <= 1e-5 * sum|w*x| per output element; where that sum is zero
+(no nonzero reaches a real input) the GPU value must be exactly zero."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1608_01409_amd import binding as B
+from paper_1608_01409_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def check(layer, w, x, oracle, plan=None, images=None, what=""):
+    """Run the library on all of x; compare the images listed (default: all) with the oracle."""
+    say(f"{what} layer={layer} N={x.shape[0]} plan={plan}")
+    h = B.sconv_create_csr(layer, w, plan)
+    info = B.sconv_csr_info(h)
+    xd = torch.from_numpy(x).cuda()
+    out = B.sconv_forward(h, xd)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    idx = np.arange(x.shape[0]) if images is None else np.asarray(images)
+    ref, ab, _ = oracle.sparse_conv(layer, w, x[idx])
+    err = np.abs(got[idx].astype(np.float64) - ref)
+    bad = err > TOL * ab
+    assert not bad.any(), (what, info["plan"], int(bad.sum()), float(err.max()), np.argwhere(bad)[:5])
+    assert np.all(got[idx][ab == 0] == 0)
+    return got, info
+
+
+def rand_case(layer, N, density, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, layer.C, layer.H, layer.W)).astype(np.float32)
+    w = (rng.standard_normal((layer.K, layer.Cg, layer.R, layer.S)) * 0.01).astype(np.float32)
+    if density < 1:
+        w = np.where(rng.random(w.shape) < density, w, np.float32(0)).astype(np.float32)
+    return x, w
+
+
+MID = wl.small_layer("mid", C=32, H=13, W=13, K=50, R=3, S=3, stride=1, pad=1, groups=2)
+
+PLANS = [
+    None,
+    dict(kernel=2),
+    dict(kernel=1, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),
+    dict(kernel=1, nt=4, cb=5, waves=4, cg=1, rows_w=4, t=3),
+    dict(kernel=1, nt=4, cb=16, waves=16, cg=1, rows_w=8, t=3),
+    dict(kernel=1, nt=8, cb=4, waves=8, cg=2, rows_w=6, t=3),
+    dict(kernel=1, nt=8, cb=4, waves=8, cg=1, rows_w=3, t=6),
+    dict(kernel=1, nt=8, cb=3, waves=4, cg=1, rows_w=2, t=6),
+    dict(kernel=1, nt=16, cb=2, waves=8, cg=4, rows_w=6, t=3),
+    dict(kernel=1, nt=1, cb=16, waves=8, cg=1, rows_w=8, t=3),
+    dict(kernel=1, nt=2, cb=16, waves=4, cg=2, rows_w=8, t=3),
+]
+
+
+@pytest.mark.parametrize("plan", PLANS, ids=[str(i) for i in range(len(PLANS))])
+def test_every_kernel_shape_on_a_ragged_batch(oracle, plan):
+    # 21 images: several tiles of 4/8/16 and a ragged last one; 25 rows per group: ragged row tiles
+    x, w = rand_case(MID, 21, 0.15, seed=31)
+    w[7] = 0
+    w[30:34] = 0
+    check(MID, w, x, oracle, plan, what="ragged")
+
+
+SHAPES = [
+    dict(C=8, H=27, W=27, K=16, R=5, S=5, stride=1, pad=2, groups=2),
+    dict(C=6, H=28, W=28, K=12, R=3, S=3, stride=1, pad=1, groups=1),
+    dict(C=4, H=28, W=28, K=12, R=5, S=5, stride=1, pad=2, groups=1),
+    dict(C=6, H=9, W=17, K=10, R=3, S=5, stride=1, pad=0, groups=1),
+    dict(C=6, H=10, W=7, K=9, R=1, S=1, stride=1, pad=0, groups=3),
+    dict(C=4, H=11, W=8, K=6, R=2, S=3, stride=1, pad=3, groups=1),
+    dict(C=3, H=35, W=35, K=8, R=11, S=11, stride=4, pad=0, groups=1),
+    dict(C=4, H=14, W=15, K=6, R=3, S=3, stride=2, pad=1, groups=2),
+    dict(C=2, H=12, W=10, K=4, R=3, S=3, stride=3, pad=2, groups=1),
+]
+
+
+@pytest.mark.parametrize("dims", SHAPES, ids=[str(i) for i in range(len(SHAPES))])
+@pytest.mark.parametrize("N", [1, 6])
+def test_layer_shapes_automatic_plan(oracle, dims, N):
+    layer = wl.small_layer("shape", **dims)
+    x, w = rand_case(layer, N, 0.3, seed=41 + N)
+    check(layer, w, x, oracle, None, what="shape")
+
+
+def test_density_one_and_zero(oracle):
+    x, w = rand_case(MID, 9, 1.0, seed=43)
+    check(MID, w, x, oracle, None, what="dense")
+    check(MID, w, x, oracle, dict(kernel=2), what="dense-direct")
+    z = np.zeros_like(w)
+    for plan in (None, dict(kernel=2)):
+        got, _ = check(MID, z, x, oracle, plan, what="all-zero")
+        assert np.all(got == 0)
+
+
+def test_linear_in_weights_on_gpu(oracle):
+    x, w1 = rand_case(MID, 8, 0.2, seed=45)
+    _, w2 = rand_case(MID, 8, 0.2, seed=46)
+    w1 = (np.round(w1 * 2 ** 16) / 2 ** 16).astype(np.float32)
+    w2 = (np.round(w2 * 2 ** 16) / 2 ** 16).astype(np.float32)
+    g1, _ = check(MID, w1, x, oracle, None, what="lin-1")
+    g2, _ = check(MID, w2, x, oracle, None, what="lin-2")
+    g12, _ = check(MID, (0.5 * w1 - 2 * w2).astype(np.float32), x, oracle, None, what="lin-12")
+    _, a1, _ = oracle.sparse_conv(MID, w1, x)
+    _, a2, _ = oracle.sparse_conv(MID, w2, x)
+    assert np.all(np.abs(g12 - (0.5 * g1.astype(np.float64) - 2 * g2)) <= 3 * TOL * (0.5 * a1 + 2 * a2))
+
+
+def test_run_to_run_bit_identical_and_output_overwritten(oracle):
+    x, w = rand_case(MID, 12, 0.15, seed=47)
+    h = B.sconv_create_csr(MID, w)
+    xd = torch.from_numpy(x).cuda()
+    out = torch.full((12, MID.K, MID.OH, MID.OW), float("nan"), device="cuda")
+    B.sconv_forward(h, xd, out)
+    a = out.clone()
+    out.fill_(123.0)
+    B.sconv_forward(h, xd, out)
+    torch.cuda.synchronize()
+    assert torch.equal(a, out) and not torch.isnan(out).any()
+
+
+def test_non_finite_inputs_stay_where_the_oracle_puts_them(oracle):
+    """Padding entries of the nonzero stream multiply zeros, never the input."""
+    x, w = rand_case(MID, 8, 0.15, seed=49)
+    x[:, :, 0, 0] = np.inf
+    x[3, 5, 6, 6] = np.nan
+    h = B.sconv_create_csr(MID, w)
+    got = B.sconv_forward(h, torch.from_numpy(x).cuda()).cpu().numpy()
+    ref, ab, _ = oracle.sparse_conv(MID, w, x)
+    fin = np.isfinite(ref)
+    assert np.array_equal(np.isfinite(got), fin)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= TOL * ab[fin])
+
+
+def test_stream_argument_is_honoured(oracle):
+    x, w = rand_case(MID, 8, 0.15, seed=51)
+    h = B.sconv_create_csr(MID, w)
+    xd = torch.from_numpy(x).cuda()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        out = B.sconv_forward(h, xd)
+    s.synchronize()
+    ref, ab, _ = oracle.sparse_conv(MID, w, x)
+    assert np.all(np.abs(out.cpu().numpy() - ref) <= TOL * ab)
+
+
+# ---------------------------------------------------------------- benchmark configurations
+def test_config0_conv3_batch1(oracle):
+    (name, N, dens), = wl.CONFIGS[0]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(0, 0, layer, N, dens)
+    check(layer, w, x, oracle, None, what="config0")
+    check(layer, w, x, oracle, dict(kernel=1, nt=1, cb=32, waves=8, cg=1, rows_w=8, t=3), what="config0-lds")
+
+
+@pytest.mark.parametrize("li", range(4))
+def test_config1_alexnet_full_batch_sampled_images(oracle, li):
+    """Full-size launch exactly as the benchmark times it; the oracle checks whole images sampled
+    from the batch (first and last tiles, tile boundaries, a few inside)."""
+    name, N, dens = wl.CONFIGS[1][li]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(1, li, layer, N, dens)
+    images = [0, 1, 3, 4, 7, 8, 100, 127, 128, 200, 252, 255]
+    check(layer, w, x, oracle, None, images=images, what=f"config1-{name}")
+
+
+@pytest.mark.parametrize("name", ["conv3", "conv4"])
+def test_config3_skewed_rows(oracle, name):
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(3, 0 if name == "conv3" else 1, layer, 64, 0.10, skewed=True)
+    nnz_row = (w.reshape(layer.K, -1) != 0).sum(1)
+    assert (nnz_row == 0).sum() >= 0.15 * layer.K and nnz_row.max() > 3 * nnz_row.mean()
+    check(layer, w, x, oracle, None, images=[0, 5, 31, 32, 63], what=f"skewed-{name}")
+
+
+@pytest.mark.parametrize("li", range(3))
+def test_config4_googlenet_like_and_strided(oracle, li):
+    name, N, dens = wl.CONFIGS[4][li]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(4, li, layer, N, dens)
+    check(layer, w, x, oracle, None, images=[0, 3, 4, 33, 63], what=f"config4-{name}")
+
+
+@pytest.mark.parametrize("dens", [0.01, 0.5, 1.0])
+def test_density_sweep_ends_on_conv5(oracle, dens):
+    layer = wl.LAYERS["conv5"]
+    x, w = wl.make_case(2, 3, layer, 32, dens)
+    check(layer, w, x, oracle, None, images=[0, 17, 31], what=f"sweep-{dens}")

@@ -1,0 +1,215 @@
+"""CPU-side tests of libsconv: the library loads and exports the C ABI, its
+lowering is bit-exact against the oracle's, the kernel packings round-trip, the
+error paths answer with status codes, and the model matches the model oracle.
+No kernel is launched here."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import perf_model_oracle as pm
+from paper_1608_01409_amd import binding as B
+from paper_1608_01409_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def rand_w(layer, density, seed):
+    rng = np.random.default_rng(seed)
+    w = rng.standard_normal((layer.K, layer.Cg, layer.R, layer.S)).astype(np.float32)
+    if density < 1:
+        w = np.where(rng.random(w.shape) < density, w, np.float32(0)).astype(np.float32)
+    return w
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sconv.h")).read()
+    declared = set(re.findall(r"\b(sconv_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert B.strerror(0) == "ok" and "CSR" in B.strerror(B.ERR["CSR"])
+
+
+CASES = [
+    (wl.small_layer(), 0.4),
+    (wl.small_layer(C=4, H=7, W=6, K=4, R=2, S=3, stride=2, pad=1, groups=2), 0.5),
+    (wl.small_layer(C=2, H=13, W=12, K=2, R=5, S=4, stride=4, pad=0, groups=1), 0.7),
+    (wl.small_layer(C=16, H=13, W=13, K=24, R=3, S=3, stride=1, pad=1, groups=2), 0.1),
+    (wl.LAYERS["conv3"], 0.1),
+    (wl.LAYERS["conv2"], 0.1),
+    (wl.LAYERS["conv5"], 0.02),
+    (wl.LAYERS["goog5x5"], 0.3),
+    (wl.LAYERS["conv1"], 0.3),
+]
+
+
+@pytest.mark.parametrize("layer,density", CASES, ids=[f"{c[0].name}-{i}" for i, c in enumerate(CASES)])
+def test_lowering_bit_exact_and_packings_round_trip(oracle, layer, density):
+    w = rand_w(layer, density, seed=3)
+    w[0, 0, 0, 0] = np.float32("nan")
+    w[layer.K - 1, 0, 0, 0] = -0.0
+    o_rowptr, o_col, o_val = oracle.csr_from_dense(layer, w)
+    o_off = oracle.lower_offsets(layer, o_rowptr, o_col)
+    h = B.sconv_create_csr(layer, w)
+    rowptr, off, val = B.sconv_csr_export(h)
+    assert np.array_equal(rowptr, o_rowptr)
+    assert np.array_equal(off, o_off)
+    assert np.array_equal(val.view(np.uint32), o_val.view(np.uint32))
+    info = B.sconv_csr_info(h)
+    assert info["nnz"] == len(o_val) and (info["OH"], info["OW"]) == (layer.OH, layer.OW)
+    which = [2] + ([1] if info["plan"]["kernel"] == 1 else [])
+    assert (info["plan"]["kernel"] == 1) == (layer.stride == 1)
+    for wh in which:
+        r2, o2, v2 = B.sconv_csr_unpack(h, wh)
+        assert np.array_equal(r2, o_rowptr) and np.array_equal(o2, o_off)
+        assert np.array_equal(v2.view(np.uint32), o_val.view(np.uint32))
+    # the same arrays through the CSR entry point
+    h2 = B.sconv_create_csr_from_arrays(layer, o_rowptr, o_col, o_val)
+    r3, o3, v3 = B.sconv_csr_export(h2)
+    assert np.array_equal(r3, o_rowptr) and np.array_equal(o3, o_off)
+    assert np.array_equal(v3.view(np.uint32), o_val.view(np.uint32))
+
+
+PLANS = [
+    dict(kernel=1, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),
+    dict(kernel=1, nt=4, cb=5, waves=4, cg=1, rows_w=4, t=3),
+    dict(kernel=1, nt=8, cb=4, waves=8, cg=2, rows_w=6, t=3),
+    dict(kernel=1, nt=8, cb=4, waves=8, cg=1, rows_w=3, t=6),
+    dict(kernel=1, nt=1, cb=16, waves=8, cg=1, rows_w=8, t=3),
+    dict(kernel=1, nt=2, cb=16, waves=4, cg=2, rows_w=8, t=3),
+]
+
+
+@pytest.mark.parametrize("plan", PLANS, ids=[str(i) for i in range(len(PLANS))])
+def test_explicit_plans_round_trip(oracle, plan):
+    layer = wl.small_layer(C=32, H=13, W=13, K=50, R=3, S=3, stride=1, pad=1, groups=2)
+    w = rand_w(layer, 0.15, seed=5)
+    w[7] = 0  # an empty row
+    o_rowptr, o_col, o_val = oracle.csr_from_dense(layer, w)
+    o_off = oracle.lower_offsets(layer, o_rowptr, o_col)
+    h = B.sconv_create_csr(layer, w, plan)
+    got = B.sconv_csr_info(h)["plan"]
+    assert got == plan
+    r, o, v = B.sconv_csr_unpack(h, 1)
+    assert np.array_equal(r, o_rowptr) and np.array_equal(o, o_off)
+    assert np.array_equal(v.view(np.uint32), o_val.view(np.uint32))
+
+
+def test_explicit_zeros_survive_the_array_entry_point():
+    layer = wl.small_layer(C=2, H=5, W=5, K=2, R=3, S=3, stride=1, pad=1, groups=1)
+    rowptr = np.array([0, 2, 3], dtype=np.int32)
+    colidx = np.array([0, 17, 4], dtype=np.int32)
+    val = np.array([0.0, 1.5, -0.0], dtype=np.float32)
+    h = B.sconv_create_csr_from_arrays(layer, rowptr, colidx, val)
+    r, o, v = B.sconv_csr_export(h)
+    assert np.array_equal(r, rowptr) and len(o) == 3
+    assert np.array_equal(v.view(np.uint32), val.view(np.uint32))
+    for wh in (1, 2):
+        r2, o2, v2 = B.sconv_csr_unpack(h, wh)
+        assert np.array_equal(o2, o) and np.array_equal(v2.view(np.uint32), val.view(np.uint32))
+
+
+def test_error_paths():
+    L = B.lib()
+    layer = wl.small_layer()
+    w = rand_w(layer, 0.5, seed=1)
+    out = C.c_void_p()
+    d = B.make_desc(layer)
+    assert L.sconv_create_csr(None, w.ctypes.data_as(C.c_void_p), None, C.byref(out)) == B.ERR["NULL"]
+    assert L.sconv_create_csr(C.byref(d), None, None, C.byref(out)) == B.ERR["NULL"]
+    assert L.sconv_create_csr(C.byref(d), w.ctypes.data_as(C.c_void_p), None, None) == B.ERR["NULL"]
+    for bad in (dict(C=0), dict(groups=3), dict(stride=0), dict(pad=-1), dict(R=20, pad=0), dict(K=5, groups=2)):
+        with pytest.raises(B.SconvError) as e:
+            B.sconv_create_csr(wl.small_layer(**bad), w)
+        assert e.value.status == B.ERR["DESC"]
+    # malformed CSR
+    ncol = layer.Cg * layer.R * layer.S
+    good_rp = np.array([0, 1, 1, 2, 2, 2, 3], dtype=np.int32)
+    cases = [
+        (np.array([1, 1, 1, 2, 2, 2, 3], dtype=np.int32), [0, 1, 2]),    # rowptr[0] != 0
+        (np.array([0, 2, 1, 2, 2, 2, 3], dtype=np.int32), [0, 1, 2]),    # not monotone
+        (good_rp, [0, ncol, 2]),                                         # column out of range
+        (good_rp, [-1, 1, 2]),
+        (np.array([0, 3, 3, 3, 3, 3, 3], dtype=np.int32), [0, 2, 2]),    # duplicate
+        (np.array([0, 3, 3, 3, 3, 3, 3], dtype=np.int32), [0, 2, 1]),    # descending
+    ]
+    for rp, ci in cases:
+        with pytest.raises(B.SconvError) as e:
+            B.sconv_create_csr_from_arrays(layer, rp, np.array(ci, dtype=np.int32), np.ones(3, dtype=np.float32))
+        assert e.value.status == B.ERR["CSR"], (rp, ci)
+    # plans that cannot run
+    with pytest.raises(B.SconvError) as e:
+        B.sconv_create_csr(wl.small_layer(stride=2), w, dict(kernel=1))
+    assert e.value.status == B.ERR["PLAN"]
+    with pytest.raises(B.SconvError) as e:
+        B.sconv_create_csr(layer, w, dict(kernel=1, nt=4, cb=4, waves=8, cg=1, rows_w=6, t=1))  # too few chunks
+    assert e.value.status == B.ERR["PLAN"]
+    with pytest.raises(B.SconvError) as e:
+        B.sconv_create_csr(layer, w, dict(kernel=1, nt=3, cb=4, waves=8, cg=1, rows_w=8, t=3))  # nt must divide 64
+    assert e.value.status == B.ERR["PLAN"]
+    # export capacity
+    h = B.sconv_create_csr(layer, w)
+    n = C.c_int64(1)
+    rp = np.zeros(layer.K + 1, dtype=np.int32)
+    one = np.zeros(1, dtype=np.int32)
+    rc = L.sconv_csr_export(h.handle, rp.ctypes.data_as(C.c_void_p), one.ctypes.data_as(C.c_void_p),
+                            one.ctypes.data_as(C.c_void_p), C.byref(n))
+    assert rc == B.ERR["CAPACITY"] and n.value == B.sconv_csr_info(h)["nnz"]
+    # forward argument checks happen before any device work
+    assert L.sconv_forward(h.handle, None, None, 1, None) == B.ERR["NULL"]
+    assert L.sconv_forward(h.handle, C.c_void_p(16), C.c_void_p(32), 0, None) == B.ERR["BATCH"]
+    assert L.sconv_forward(None, C.c_void_p(16), C.c_void_p(32), 1, None) == B.ERR["NULL"]
+
+
+def test_automatic_plans_for_the_benchmark_layers():
+    for name in ("conv2", "conv3", "conv4", "conv5", "goog3x3", "goog5x5"):
+        layer = wl.LAYERS[name]
+        h = B.sconv_create_csr(layer, rand_w(layer, 0.1, seed=2))
+        p = B.sconv_csr_info(h)["plan"]
+        assert p["kernel"] == 1 and p["nt"] % 4 == 0, (name, p)
+    h = B.sconv_create_csr(wl.LAYERS["conv1"], rand_w(wl.LAYERS["conv1"], 0.3, seed=2))
+    assert B.sconv_csr_info(h)["plan"]["kernel"] == 2
+
+
+# ------------------------------------------------------------------ model
+def test_model_matches_oracle_with_paper_machine():
+    layer = wl.LAYERS["conv5"]
+    for (F, Bw, alpha) in [(2150e9, 122e9, 3.0), (62e9, 15e9, 1.2)]:
+        m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0)
+        for N in (1, 144):
+            for x in (0.001, 0.0197, 0.09, 0.3, 1.0):
+                got = B.sconv_model_predict(layer, N, x, machine=m)
+                ref = pm.predict(layer, N, x, F, Bw, alpha, 2.0)
+                for key, val in ref.items():
+                    g = got[key]
+                    if isinstance(val, bool):
+                        assert bool(g) == val, key
+                    elif math.isinf(val):
+                        assert math.isinf(g)
+                    else:
+                        assert math.isclose(g, val, rel_tol=1e-12), (key, g, val)
+
+
+def test_model_derived_alpha_and_realised_density():
+    layer = wl.LAYERS["conv3"]
+    m = B.sconv_machine_gfx950()
+    assert m.alpha <= 0 and m.beta == 2.0
+    a = pm.derive_alpha(m.dense_flops, m.fma_flops, m.lds_bytes_per_s, m.lds_bytes_per_fma, m.lane_efficiency)
+    w = rand_w(layer, 0.1, seed=9)
+    h = B.sconv_create_csr(layer, w)
+    x = np.count_nonzero(w) / w.size
+    got = B.sconv_model_predict(layer, 256, 0.5, csr=h)     # density argument replaced by the handle's
+    ref = pm.predict(layer, 256, x, m.dense_flops, m.hbm_bytes_per_s, a, m.beta)
+    assert math.isclose(got["density"], x, rel_tol=1e-12)
+    for key in ("alpha", "t_dense", "t_sparse", "speedup", "x_upper", "x_lower", "actual_flops"):
+        assert math.isclose(got[key], ref[key], rel_tol=1e-12), key
+    L = B.lib()
+    p = B.sconv_prediction()
+    d = B.make_desc(layer)
+    assert L.sconv_model_predict(C.byref(d), 0, 0.1, None, None, C.byref(p)) == B.ERR["BATCH"]
+    assert L.sconv_model_predict(C.byref(d), 1, 0.1, None, None, None) == B.ERR["NULL"]
