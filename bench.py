@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Benchmark of the direct-sparse-convolution hot path on one MI355X.
+
+A step is one forward pass of AlexNet conv2, conv3, conv4 and conv5 (batch 256,
+10 % nonzero density, seeded synthetic weights and activations already resident
+in HBM) through the C-ABI library.  The metric is the rate of useful
+multiply-adds, 2*nnz*OH*OW*N FLOP per layer (nonzeros only; the paper calls
+this the actual FLOP/s, Section 3.2), summed over the four layers and divided
+by the wall time of the step.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# plain v_fma_f32: 256 CUs x 4 SIMDs x 16 lanes x 2 FLOP x 2.4 GHz (packed FP32 would double it)
+PEAK_FMA_TFLOPS = 78.6
+PEAK_FP32_PUBLISHED_TFLOPS = 157.3
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (batch-sharded data parallelism needs no "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1608_01409_amd import binding as B
+    from paper_1608_01409_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    layers = []
+    for li, (name, N, dens) in enumerate(wl.CONFIGS[1]):
+        layer = wl.LAYERS[name]
+        x, w = wl.make_case(1, li, layer, N, dens)
+        h = B.sconv_create_csr(layer, w)
+        info = B.sconv_csr_info(h)
+        xd = torch.from_numpy(x).cuda()
+        out = torch.empty((N, layer.K, info["OH"], info["OW"]), dtype=torch.float32, device="cuda")
+        flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
+        dense_flops = 2.0 * layer.K * layer.Cg * layer.R * layer.S * info["OH"] * info["OW"] * N
+        layers.append(dict(name=name, layer=layer, N=N, h=h, x=xd, out=out, flops=flops, dense_flops=dense_flops,
+                           plan=info["plan"], nnz=info["nnz"], host=(x, w)))
+
+    def step(events=None):
+        for i, L in enumerate(layers):
+            if events is not None:
+                events[i][0].record(stream)
+            B.sconv_forward(L["h"], L["x"], L["out"], stream=stream)
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    total_flops = sum(L["flops"] for L in layers)
+    value = total_flops / (ms_per_step * 1e-3) / 1e9
+
+    per_layer = []
+    for i, L in enumerate(layers):
+        ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
+        tf = L["flops"] / (ms * 1e-3) / 1e12
+        per_layer.append(dict(layer=L["name"], kernel_us=round(ms * 1e3, 2), tflops=round(tf, 3),
+                              effective_tflops=round(L["dense_flops"] / (ms * 1e-3) / 1e12, 2),
+                              frac_of_fma_peak=round(tf / PEAK_FMA_TFLOPS, 4), nnz=L["nnz"], plan=L["plan"]))
+    dom = max(range(len(layers)), key=lambda i: per_layer[i]["kernel_us"])
+    achieved = per_layer[dom]["tflops"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(layers[dom]["name"])
+        except (OSError, ValueError):
+            traffic = None
+    roofline = dict(bound="alu", achieved=achieved, peak=PEAK_FMA_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_FMA_TFLOPS, 4), traffic=traffic,
+                    kernel=f"sconv_lds_kernel on {layers[dom]['name']}",
+                    frac_of_published_fp32_vector=round(achieved / PEAK_FP32_PUBLISHED_TFLOPS, 4),
+                    step_frac=round(value / 1e3 / PEAK_FMA_TFLOPS, 4), per_layer=per_layer)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sconv_oracle as O
+        t_cpu, used, reps = 0.0, 0, 0
+        csr = []
+        for L in layers:
+            x, w = L["host"]
+            rp, ci, v = O.csr_from_dense(L["layer"], w)
+            csr.append((rp, O.lower_offsets(L["layer"], rp, ci), v))
+        while t_cpu < 10.0 and reps < 20:
+            for L, (rp, off, v) in zip(layers, csr):
+                a = time.perf_counter()
+                _, used = O.forward_f32(L["layer"], rp, off, v, L["host"][0])
+                t_cpu += time.perf_counter() - a
+            reps += 1
+        cpu = dict(value=round(total_flops * reps / t_cpu / 1e9, 2), unit="GFLOP/s", cores=used, kind="oracle",
+                   sample=f"the whole step (conv2-5, batch 256) x {reps} repetitions, fp32 loop of Figure 2, OpenMP")
+
+    print(json.dumps({
+        "metric": "effective GFLOP/s (2*nnz*OH*OW*N/s), AlexNet conv2-5 @ 10% density",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "AlexNet conv2-conv5, batch 256, fp32, Bernoulli masks at density 0.10 "
+                               "(BASELINE.json configs[1])", "global_batch": 256,
+                   "dense_equivalent_gflops": round(sum(L["dense_flops"] for L in layers) / (ms_per_step * 1e-3) / 1e9, 1)},
+        "roofline": roofline, "cpu_baseline": cpu}))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

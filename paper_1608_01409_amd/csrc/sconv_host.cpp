@@ -122,35 +122,39 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     const int kt = t.rg * p.rows_w;
     t.nkt = ceil_div(g.Kg, kt);
     t.wave_slots = d.groups * t.nkt * t.rg;
-    t.items = t.plane_cells * p.nt / t.vec;
-    const int threads = p.waves * 64;
-    int grp = 64;
-    while (grp < t.items && grp < threads) grp *= 2;
-    if (grp > threads) grp = threads; // waves not a power of two: fall back to the whole workgroup
-    if (threads % grp) grp = 64;
-    t.stage_group = grp;
-    if (ceil_div(t.items, grp) > 4) return SCONV_ERR_PLAN; // items one thread stages per channel
-    // LDS layout in floats: [staged block: cb*plane_cells*nt][zero page: cg*t*64*vec].  The zero page is
-    // cleared once per launch and never written.  It serves three readers: the right padding of the very
-    // last row (pad*nt floats past the block), lanes past the last valid position (their results are
-    // dropped), and the padding entries of the nonzero stream, whose offset is the page's start, so that
-    // they multiply 0 by 0 for every lane and chunk.
-    const int64_t staged = (int64_t)t.p.cb * t.plane_cells * p.nt;
+    const int plane_floats = t.plane_cells * p.nt;
+    t.n_slabs = ceil_div(plane_floats, 64);
+    if (ceil_div(t.n_slabs, p.waves) > 4) return SCONV_ERR_PLAN; // slabs one wave stages per channel
+    // LDS layout in floats: n_bufs x { [block: cb*plane_cells*nt] [zero page: cg*t*64*vec] }.  The zero
+    // pages are cleared once per launch and never written.  A page serves three readers of the block in
+    // front of it: the right padding of the very last row (pad*nt floats past the block), lanes past the
+    // last valid position (their results are dropped), and the padding entries of the nonzero stream,
+    // whose offset is the page's start, so that they multiply 0 by 0 for every lane and chunk.
+    const int64_t block = (int64_t)t.p.cb * plane_floats;
     const int64_t page = (int64_t)p.cg * p.t * 64 * t.vec;
     if (page < (int64_t)d.pad * p.nt) return SCONV_ERR_PLAN;
-    int64_t floats = staged + page;
-    floats = (floats + 3) / 4 * 4;
-    if (floats * 4 > 160 * 1024) return SCONV_ERR_PLAN;
-    t.lds_bytes = (int)(floats * 4);
-    t.staged_floats = (int)staged;
-    t.zero_page = (unsigned)(staged * 4);
-    // byte offsets (value pairs) and per-wave chunk offsets must stay below 2^31; trivially true here.
+    const int64_t stride = (block + page + 3) / 4 * 4;
+    t.n_bufs = t.nblk > 1 ? 2 : 1;
+    if (stride * t.n_bufs * 4 > 160 * 1024) return SCONV_ERR_PLAN;
+    t.buf_stride_floats = (int)stride;
+    t.lds_bytes = (int)(stride * t.n_bufs * 4);
+    t.zero_page = (unsigned)(block * 4);
     return SCONV_OK;
 }
 
 // Supported accumulator shapes; must match the instantiations in sconv_kernels.hip.
 static const int kShapesV4[][2] = {{1, 8}, {2, 4}, {2, 8}, {3, 4}, {3, 6}, {3, 8}, {4, 4}, {4, 6}, {5, 4},
                                    {6, 2}, {6, 3}, {7, 2}, {7, 3}, {13, 1}, {14, 1}};
+// read-ahead depth (stream entries in flight) of each shape above, as generated by gen_lds_loops.py
+static const int kDepthV4[] = {4, 4, 2, 4, 2, 1, 2, 1, 1, 2, 1, 2, 1, 1, 1};
+
+static int shape_depth(int vec, int t, int rows_w)
+{
+    if (vec != 4) return 1;
+    for (size_t i = 0; i < sizeof(kDepthV4) / sizeof(kDepthV4[0]); ++i)
+        if (kShapesV4[i][0] == t && kShapesV4[i][1] == rows_w) return kDepthV4[i];
+    return 1;
+}
 static const int kShapesV1[][2] = {{1, 16}, {2, 16}, {3, 8}, {3, 16}, {4, 8}, {7, 8}, {13, 4}, {14, 4}};
 
 bool lds_kernel_available(int vec, int t, int rows_w)
@@ -175,16 +179,23 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
     const int by_waves = std::max(1, 16 / t.p.waves);
     const int wpc = std::min(by_lds, by_waves);
     const double rows_per_wave = (double)g.Kg / (t.nkt * t.rg); // after dealing rows evenly
-    const double nnz_wave = rows_per_wave * avg_row_nnz;
+    // every (row, block) segment is padded to whole chunks: 1.5 entries on average
+    const double seg_len = std::max(0.25, avg_row_nnz / t.nblk);
+    const double nnz_wave = rows_per_wave * avg_row_nnz * (seg_len + 1.5) / seg_len;
     const double fma_instr = t.p.t * t.vec;
     // SIMD-issue bound: waves on a SIMD run one after another; 4 clocks per wave instruction.
-    const double simd = std::ceil(t.p.waves / 4.0) * nnz_wave * 4.0 * (fma_instr + 2.0);
+    // a shallow read-ahead ring leaves the wave waiting on LDS latency more often
+    const double ring = 1.0 + 2.0 / (shape_depth(t.vec, t.p.t, t.p.rows_w) * t.p.t);
+    const double simd = std::ceil(t.p.waves / 4.0) * nnz_wave * 4.0 * (fma_instr + 2.0) * ring;
     // LDS bound: clocks per wave read instruction.
     const double lds = t.p.waves * nnz_wave * t.p.t * (t.vec == 4 ? 4.3 : 2.4);
     // per segment fixed costs (pointer fetch, loop set-up, scalar latency), per wave, partly hidden
     const double seg = (double)t.nblk * t.p.rows_w * 60.0 * std::ceil(t.p.waves / 4.0);
-    const double stage = (double)g.Cg * t.plane_cells * t.p.nt * 4.0 / 48.0 + t.nblk * 1500.0;
-    const double wg = std::max(simd, lds) + seg + stage / wpc;
+    // loads stream in behind the multiply-adds; only the first block's load is exposed
+    const double stage = (double)t.p.cb * t.plane_cells * t.p.nt * 4.0 / 32.0 + 3000.0 + t.nblk * 300.0;
+    // fewer than four waves per SIMD hide each other's stalls less well
+    const double occ = std::sqrt(16.0 / std::min(16, t.p.waves * wpc));
+    const double wg = std::max(simd, lds) * occ + seg + stage;
     const double rounds = std::ceil(wgs / (256.0 * wpc));
     return rounds * wpc * wg;
 }
@@ -225,10 +236,11 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                     if (req.rows_w && req.rows_w != rows_w) continue;
                     for (int wpc_target : {1, 2, 4}) {
                         if (waves * wpc_target > 16) continue;
-                        const int budget = 160 * 1024 / wpc_target - 1024;
+                        const int budget = 160 * 1024 / wpc_target - 256;
                         const int64_t per_ch = (int64_t)g.Hp * Wl * nt * 4;
                         const int64_t fixed = (int64_t)cg * T * 64 * vec * 4 + 16;
-                        int cb = (int)std::min<int64_t>(g.Cg, (budget - fixed) / per_ch + 0);
+                        int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
+                        if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
                         if (req.cb) cb = req.cb;
                         if (cb < 1) continue;
                         // even out the blocks

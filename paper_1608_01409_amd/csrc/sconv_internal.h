@@ -51,11 +51,11 @@ struct LdsTiling {
     int rg;             // row groups = waves / cg
     int nkt;            // K tiles per group
     int wave_slots;     // groups * nkt * rg
-    int items;          // staging items per channel: plane_cells * nt / vec
-    int stage_group;    // threads that cooperate on one channel (power of two)
+    int n_slabs;        // 64-float slabs per channel plane (staging granule)
+    int n_bufs;         // LDS block buffers: 2 (double-buffered) unless the layer is a single block
+    int buf_stride_floats; // floats from one buffer to the next: block + zero page, multiple of 4
     int lds_bytes;      // dynamic LDS per workgroup
-    int staged_floats;  // cb * plane_cells * nt: what staging writes; everything after it stays zero
-    unsigned zero_page; // byte offset of a region that is zero for every lane and chunk (padding entries)
+    unsigned zero_page; // byte offset, relative to a buffer, of its all-zero page (padding entries)
 };
 
 struct PackedLds {

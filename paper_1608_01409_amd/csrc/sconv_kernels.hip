@@ -26,11 +26,13 @@ struct LdsArgs {
     const int *row_of;
     int N, C, H, W, K, OH, OW, pad, Cg, groups;
     int nt, cb, nblk, rg, cg, nkt;
-    int Wl, plane_cells, items, stage_group_log2, lds_floats, staged_floats;
+    int Wl, plane_floats, n_slabs, buf_stride_floats, lds_floats;
     int n_tiles, units;
 };
 
-constexpr int kMaxItemsPerThread = 4;
+constexpr int kMaxSlabsPerWave = 4; // 64-float slabs of a channel plane one wave stages
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void global_void_t;
 constexpr int kGroup = SCONV_PAIR_GROUP; // nonzeros per straight-line group; segments are padded to it
 using const_u32 = const __attribute__((address_space(4))) unsigned;
 
@@ -75,68 +77,68 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
     const int CHW = a.C * HW;
     const float *in_tile = a.in + (size_t)n0 * CHW;
 
-    // ---- staging set-up: this thread always handles the same cells, for every channel and block.
-    const int G = 1 << a.stage_group_log2;
-    const int tg = tid & (G - 1);
-    const int csub = tid >> a.stage_group_log2;
-    const int n_par = (int)blockDim.x >> a.stage_group_log2;
-    const int q_cnt = a.nt / VEC;
-    int src_off[kMaxItemsPerThread]; // offset of (first image of the lane, channel 0, iy, ix) in the tile, -1: padding, -2: no item
-    int img0[kMaxItemsPerThread];
+    // ---- staging set-up.  A channel plane in LDS is plane_floats = cells*nt floats, image innermost.  It is
+    // filled 64 floats at a time by global_load_lds_dword: lane l of the instruction for slab s loads the
+    // float (cell, image) = divmod(s*64 + l, nt) from its own global address and the hardware writes it to
+    // LDS at (M0 base) + l*4, with no VGPR and no VALU work, asynchronously (vmcnt).  Lanes whose cell is
+    // padding, whose image is past the batch or whose float is past the plane are masked off and their LDS
+    // words keep the zero written once below.  A wave always stages the same slabs, so the per-lane source
+    // offsets are computed once.
+    const int n_waves = (int)blockDim.x >> 6;
+    int src_off[kMaxSlabsPerWave];
 #pragma unroll
-    for (int ii = 0; ii < kMaxItemsPerThread; ++ii) {
-        const int item = tg + ii * G;
-        src_off[ii] = -2;
-        img0[ii] = 0;
-        if (item < a.items) {
-            const int cell = item / q_cnt, q = item - cell * q_cnt;
-            const int Y = cell / a.Wl, X = cell - Y * a.Wl;
-            const int iy = Y - a.pad, ix = X - a.pad;
-            const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-            img0[ii] = q * VEC;
-            src_off[ii] = inside ? q * VEC * CHW + iy * a.W + ix : -1;
-        }
+    for (int j = 0; j < kMaxSlabsPerWave; ++j) {
+        const int f = (wave + j * n_waves) * 64 + lane;
+        const int cell = f / a.nt, img = f - cell * a.nt;
+        const int Y = cell / a.Wl, X = cell - Y * a.Wl;
+        const int iy = Y - a.pad, ix = X - a.pad;
+        const bool ok = f < a.plane_floats && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W && n0 + img < a.N;
+        src_off[j] = ok ? img * CHW + iy * a.W + ix : -1;
     }
-    for (int i = a.staged_floats + tid; i < a.lds_floats; i += blockDim.x) lds[i] = 0.f;
+    {
+        float4 *z = reinterpret_cast<float4 *>(lds);
+        for (int i = tid; i < a.lds_floats / 4; i += blockDim.x) z[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __syncthreads();
+
+    auto stage = [&](int b, int buf) {
+        const int c0 = g * a.Cg + b * a.cb;
+        const int cb_here = min(a.cb, a.Cg - b * a.cb);
+#pragma unroll
+        for (int j = 0; j < kMaxSlabsPerWave; ++j) {
+            const int slab = wave + j * n_waves;
+            if (slab >= a.n_slabs) break;
+            if (src_off[j] >= 0) {
+                for (int cl = 0; cl < cb_here; ++cl) {
+                    const float *src = in_tile + (size_t)(c0 + cl) * HW + src_off[j];
+                    float *dst = lds + buf * a.buf_stride_floats + cl * a.plane_floats + slab * 64;
+                    __builtin_amdgcn_global_load_lds((global_void_t *)src, (lds_void_t *)dst, 4, 0, 0);
+                }
+            }
+        }
+    };
 
     // acc[(i*T + t)*VEC + e]: row i of this wave, chunk t, image e of the lane's quad
     float acc[ROWS_W * T * VEC];
 #pragma unroll
     for (int i = 0; i < ROWS_W * T * VEC; ++i) acc[i] = 0.f;
 
-    const unsigned lane_byte = (unsigned)((cgi * T * 64 + lane) * VEC * 4);
+    const unsigned lane_byte0 = (unsigned)((cgi * T * 64 + lane) * VEC * 4);
     const char *lds_bytes = reinterpret_cast<const char *>(lds);
     // the nonzero stream is read-only for the whole launch: constant address space => scalar loads
     const_u32 *cp = (const_u32 *)(a.pairs);
     const_u32 *cseg = (const_u32 *)(a.seg_ptr);
     const_u32 *crow = (const_u32 *)(a.row_of);
 
+    // Double-buffered: while block b is being multiplied out of buffer b&1, block b+1 streams into the
+    // other buffer.  One barrier per block: past it every wave's loads of block b have landed and every
+    // wave has finished with the buffer that block b+1 is about to overwrite.
+    stage(0, 0);
     for (int b = 0; b < a.nblk; ++b) {
-        const int c0 = g * a.Cg + b * a.cb;
-        const int cb_here = min(a.cb, a.Cg - b * a.cb);
-        if (b > 0) __syncthreads();
-        for (int cl = csub; cl < cb_here; cl += n_par) {
-            // uniform part of the address (image e of the lane's quad, channel) stays in SGPRs
-            const float *chan = in_tile + (size_t)(c0 + cl) * HW;
-#pragma unroll
-            for (int ii = 0; ii < kMaxItemsPerThread; ++ii) {
-                if (src_off[ii] == -2) continue;
-                float v[VEC];
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const bool ok = src_off[ii] >= 0 && n0 + img0[ii] + e < a.N;
-                    const float *pe = chan + (size_t)e * CHW;
-                    v[e] = ok ? pe[src_off[ii]] : 0.f;
-                }
-                const int item = tg + ii * G;
-                vec_t *dst = reinterpret_cast<vec_t *>(lds) + (cl * a.items + item);
-                if constexpr (VEC == 4)
-                    *dst = make_float4(v[0], v[1], v[2], v[3]);
-                else
-                    *dst = v[0];
-            }
-        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (b + 1 < a.nblk) stage(b + 1, (b + 1) & 1);
+        const unsigned lane_byte = lane_byte0 + (unsigned)((b & 1) * a.buf_stride_floats * 4);
 
         // Nonzeros of this wave's rows inside this channel block.  Every (row, block) segment is padded
         // on the host to whole chunks of kGroup entries (padding: value 0 at an all-zero LDS page).
@@ -287,18 +289,15 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
     a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.pad = d.pad;
     a.Cg = g.Cg; a.groups = d.groups;
     a.nt = t.p.nt; a.cb = t.p.cb; a.nblk = t.nblk; a.rg = t.rg; a.cg = t.p.cg; a.nkt = t.nkt;
-    a.Wl = t.Wl; a.plane_cells = t.plane_cells; a.items = t.items;
-    int lg = 0;
-    while ((1 << lg) < t.stage_group) ++lg;
-    a.stage_group_log2 = lg;
+    a.Wl = t.Wl; a.plane_floats = t.plane_cells * t.p.nt; a.n_slabs = t.n_slabs;
+    a.buf_stride_floats = t.buf_stride_floats;
     a.lds_floats = t.lds_bytes / 4;
-    a.staged_floats = t.staged_floats;
     a.n_tiles = (N + t.p.nt - 1) / t.p.nt;
     a.units = d.groups * t.nkt;
     // the kernel's own assumptions, checked before anything is launched
-    if ((1 << lg) != t.stage_group || (t.items + t.stage_group - 1) / t.stage_group > kMaxItemsPerThread) return SCONV_ERR_PLAN;
+    if ((t.n_slabs + t.p.waves - 1) / t.p.waves > kMaxSlabsPerWave) return SCONV_ERR_PLAN;
     if ((int64_t)t.p.nt * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;
-    if (a.staged_floats > a.lds_floats) return SCONV_ERR_PLAN;
+    if (t.lds_bytes % 16 || t.lds_bytes > 160 * 1024) return SCONV_ERR_PLAN;
     const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;

@@ -59,8 +59,8 @@ PLANS = [
     dict(kernel=1, nt=4, cb=16, waves=16, cg=1, rows_w=8, t=3),
     dict(kernel=1, nt=8, cb=4, waves=8, cg=2, rows_w=6, t=3),
     dict(kernel=1, nt=8, cb=4, waves=8, cg=1, rows_w=3, t=6),
-    dict(kernel=1, nt=8, cb=3, waves=4, cg=1, rows_w=2, t=6),
-    dict(kernel=1, nt=16, cb=2, waves=8, cg=4, rows_w=6, t=3),
+    dict(kernel=1, nt=8, cb=3, waves=8, cg=1, rows_w=2, t=6),
+    dict(kernel=1, nt=16, cb=2, waves=16, cg=4, rows_w=6, t=3),
     dict(kernel=1, nt=1, cb=16, waves=8, cg=1, rows_w=8, t=3),
     dict(kernel=1, nt=2, cb=16, waves=4, cg=2, rows_w=8, t=3),
 ]
