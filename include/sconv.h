@@ -52,13 +52,17 @@ typedef struct {
 
 /*
  * How the kernels tile a layer.  Zero in every field asks the library to choose.
- * kernel: 1 = LDS-tiled kernel (stride 1), 2 = direct kernel (any stride).
- * For the LDS-tiled kernel one workgroup owns `nt` images (1, or a multiple of
- * 4) and `waves/cg * rows_w` CSR rows; it walks the input channels in blocks of
- * `cb`; each wave keeps rows_w x t x (4 if nt >= 4 else 1) accumulators per lane.
+ * kernel: 1 = LDS-tiled kernel with one nonzero stream per row (stride 1),
+ * 3 = LDS-tiled kernel with one stream per wave (stride 1, nt = 4),
+ * 2 = direct kernel (any stride).
+ * For the LDS-tiled kernels one workgroup owns `nt` images (1, or a multiple of
+ * 4), a band of `band` consecutive output rows (0 = choose; OH = the whole
+ * image) and `waves/cg * rows_w` CSR rows; it walks the input channels in
+ * blocks of `cb`; each wave keeps rows_w x t x (4 if nt >= 4 else 1)
+ * accumulators per lane.
  */
 typedef struct {
-    int32_t kernel, nt, cb, waves, cg, rows_w, t;
+    int32_t kernel, nt, cb, waves, cg, rows_w, t, band;
 } sconv_plan;
 
 typedef struct sconv_csr sconv_csr; /* opaque, owned by the library */

@@ -16,6 +16,7 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang"
 
 def build(verbose: bool = False) -> str:
     subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_lds_loops.py")])
+    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_lds2.py")])
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip", *DEVICE_FLAGS,
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,

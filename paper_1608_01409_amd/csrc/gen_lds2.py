@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Writes sconv_lds2_asm.inc: the body of the flat-stream LDS kernel, one asm statement per
+accumulator shape (T chunks of 64 positions x 4 images per lane, R rows per wave).
+
+Everything between the first and the last multiply-add of a workgroup's tile runs inside this one
+statement, because the accumulators live in a contiguous block of fixed VGPRs that is addressed
+through the VGPR index mode (s_set_gpr_idx_on): the row an entry of the nonzero stream belongs to is
+data, not code, so the rows of a wave share one stream with no per-row padding.
+
+  stream   per (wave slot, channel block): chunks of 8 entries of 8 bytes,
+           word0 = fp32 weight, word1 = (LDS byte offset << 8) | (row * T * 4).
+           Three chunk buffers A (in use), B (next, valid), N (loading); the loop body is unrolled
+           three times with the names rotated, so no register moves are needed.
+  reads    entry p reads T float4 at lane_base + offset + t*1024 (ds_read_b128); the reads of entry
+           p + D are issued while entry p is multiplied (ring of D*T float4).  LDS returns in order,
+           so the oldest read is complete once lgkmcnt <= D*T - 1; the scalar load of chunk N only
+           makes that wait stricter, and lgkmcnt(0) at the end of a chunk makes N valid.
+  fma      v_fmac_f32 acc(t, e), weight (SGPR), ring(t, e) with the destination indexed by M0.
+  staging  block b+1 streams from global memory straight into the other LDS buffer
+           (buffer_load_dword ... lds, one instruction per 64 floats, no VGPR data) while block b is
+           multiplied.  Lanes whose cell is zero padding carry an out-of-range buffer offset and
+           receive 0 from the hardware's range check; lanes past the end of a plane are masked off.
+  stores   row bases from row_of, per-lane store offsets from a table (-1 = not an output).
+"""
+from __future__ import annotations
+
+import os
+import sys
+
+# (T, R, D, batch): batch = compute the 8 read addresses of a chunk at once (8 address VGPRs) instead of
+# one at a time with the index mode toggled off and on around each (D address VGPRs, for shapes short of VGPRs)
+SHAPES = [
+    (1, 16, 4, True), (2, 8, 4, True), (2, 12, 1, True), (3, 4, 4, True), (3, 6, 2, True), (3, 8, 1, True),
+    (4, 4, 2, True), (4, 5, 1, True), (5, 3, 2, True), (5, 4, 1, True), (6, 3, 1, True), (7, 2, 2, False),
+    (7, 3, 1, False), (13, 1, 1, False),
+]
+CH = 8                      # entries per chunk
+W = 2 * CH                  # dwords per chunk
+# SGPRs owned by the asm: s28-s31, s34-s95 (s32/s33 and everything from s96 up are left to the compiler)
+SCB, SREM, SSOFF = 28, 29, 30
+SEXEC = 34
+SA, SB, SN = 36, 52, 68
+SPTR, SCNT, STMP = 84, 86, 87
+SBLK, SNBLK, SSEG = 88, 89, 90
+SBUF, SSTRIDE, SPLANE, SHW4 = 92, 93, 94, 95
+SD, SS, SNCH, STGT = SA, SA + 1, SA + 2, SA + 3   # staging temporaries: the chunk buffers are idle then
+SX0, SX1 = SSEG, SSEG + 1                        # store address pair: the segment pointer is done by then
+MAX_VGPR = 128
+
+# kernel-argument offsets the asm reads (checked by static_asserts next to the struct)
+OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
+
+OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase", "slab0", "slabstep", "nslab",
+       "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff"]
+OP = {n: f"%{i}" for i, n in enumerate(OPS)}
+
+
+def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
+    assert CH % D == 0 and R * T * 4 <= 256
+    nacc = R * T * 4
+    ring_regs = D * T * 4
+    n_va = CH if batch else D
+    total = nacc + ring_regs + n_va + 4
+    base = (MAX_VGPR - total) & ~3
+    assert base >= 8, (T, R, D, base)
+    ACC0 = base
+    RING0 = ACC0 + nacc
+    VA0 = RING0 + ring_regs
+    VLB = VA0 + n_va        # lane base for the current buffer
+    assert VLB + 1 <= MAX_VGPR
+
+    def q(slot, t, e=None):
+        b = RING0 + (slot * T + t) * 4
+        return f"v[{b}:{b + 3}]" if e is None else f"v{b + e}"
+
+    def w0(buf, u):
+        return f"s{buf + 2 * u}"
+
+    def w1(buf, u):
+        return f"s{buf + 2 * u + 1}"
+
+    L = []
+    emit = L.append
+    uid = [0]
+
+    def label(stem):
+        uid[0] += 1
+        return f".L{stem}{uid[0]}_%="
+
+    def stage(tgt):
+        """Issue the DMA loads of the next block (channels SSOFF.. , min(SCB, SREM) of them) into LDS at tgt."""
+        emit(f"s_min_u32 s{SNCH}, s{SCB}, s{SREM}")
+        emit(f"s_add_u32 s{STMP}, s{tgt}, {OP['slab0']}")
+        end = label("stend")
+        for j in range(4):
+            emit(f"s_cmp_le_u32 {OP['nslab']}, {j}")
+            emit(f"s_cbranch_scc1 {end}")
+            emit(f"v_cmp_ne_u32_e32 vcc, -1, {OP['voff%d' % j]}")
+            emit("s_mov_b64 exec, vcc")
+            emit(f"s_mov_b32 s{SD}, s{STMP}")
+            emit(f"s_mov_b32 s{SS}, s{SSOFF}")
+            emit(f"s_mov_b32 s{SCNT}, s{SNCH}")
+            lp = label("stj")
+            emit(f"{lp}:")
+            emit(f"s_mov_b32 m0, s{SD}")
+            emit(f"s_add_u32 s{SD}, s{SD}, s{SPLANE}")
+            emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
+            emit(f"s_add_u32 s{SS}, s{SS}, s{SHW4}")
+            emit(f"s_sub_u32 s{SCNT}, s{SCNT}, 1")
+            emit(f"s_cmp_lg_u32 s{SCNT}, 0")
+            emit(f"s_cbranch_scc1 {lp}")
+            emit(f"s_add_u32 s{STMP}, s{STMP}, {OP['slabstep']}")
+        emit(f"{end}:")
+        emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
+        emit(f"s_mul_i32 s{STMP}, s{SNCH}, s{SHW4}")
+        emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{STMP}")
+        emit(f"s_sub_u32 s{SREM}, s{SREM}, s{SNCH}")
+
+    def body(A, B, N):
+        """One chunk: multiply the 8 entries of A; reads of the entries D ahead (A's tail, B's head) are issued."""
+        def entry_w1(p):
+            return w1(A, p) if p < CH else w1(B, p - CH)
+        emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], 0x0")
+        emit(f"s_add_u32 s{SPTR}, s{SPTR}, {hex(4 * W)}")
+        emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
+        if batch:
+            for j in range(CH):
+                emit(f"s_lshr_b32 s{STMP}, {entry_w1(j + D)}, 8")
+                emit(f"v_add_u32 v{VA0 + j}, s{STMP}, v{VLB}")
+        for u in range(CH):
+            slot = u % D
+            va = VA0 + (u if batch else slot)
+            if not batch:
+                emit(f"s_lshr_b32 s{STMP}, {entry_w1(u + D)}, 8")
+                emit(f"v_add_u32 v{va}, s{STMP}, v{VLB}")
+            emit(f"s_set_gpr_idx_on {w1(A, u)}, gpr_idx(DST)")
+            for t in range(T):
+                emit(f"s_waitcnt lgkmcnt({D * T - 1})")
+                for e in range(4):
+                    emit(f"v_fmac_f32 v{ACC0 + t * 4 + e}, {w0(A, u)}, {q(slot, t, e)}")
+                emit(f"ds_read_b128 {q(slot, t)}, v{va} offset:{t * 1024}")
+            if not batch:
+                emit("s_set_gpr_idx_off")
+        if batch:
+            emit("s_set_gpr_idx_off")
+        emit("s_waitcnt lgkmcnt(0)")
+        emit(f"s_sub_u32 s{SCNT}, s{SCNT}, 1")
+        emit(f"s_cmp_lg_u32 s{SCNT}, 0")
+
+    # ------------------------------------------------------------------ set-up
+    emit(f"s_mov_b64 s[{SEXEC}:{SEXEC + 1}], exec")
+    for n in range(nacc):
+        emit(f"v_mov_b32 v{ACC0 + n}, 0")
+    emit(f"s_load_dwordx8 s[{SN}:{SN + 7}], {OP['kern']}, {hex(OFF_CONSTS)}")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit(f"s_mov_b32 s{SCB}, s{SN}")
+    emit(f"s_mov_b32 s{SNBLK}, s{SN + 1}")
+    emit(f"s_mov_b32 s{SREM}, s{SN + 2}")
+    emit(f"s_mov_b32 s{SPLANE}, s{SN + 3}")
+    emit(f"s_mov_b32 s{SSTRIDE}, s{SN + 4}")
+    emit(f"s_mov_b32 s{SHW4}, s{SN + 5}")
+    emit(f"s_mov_b32 s{SSOFF}, {OP['soff0']}")
+    emit(f"s_mov_b32 s{SBLK}, 0")
+    emit(f"s_mov_b64 s[{SSEG}:{SSEG + 1}], {OP['segp']}")
+    emit(f"s_mov_b32 s{SBUF}, 0")
+    emit(f"s_mov_b32 s{STGT}, {OP['ldsbase']}")
+    stage(STGT)
+
+    # ------------------------------------------------------------------ channel blocks
+    blk, nostage, segdone = label("blk"), label("nostage"), label("segdone")
+    emit(f"{blk}:")
+    emit(f"s_load_dwordx2 s[{SN}:{SN + 1}], s[{SSEG}:{SSEG + 1}], 0x0")
+    emit(f"s_load_dwordx2 s[{SN + 2}:{SN + 3}], {OP['kern']}, {hex(OFF_PAIRS)}")
+    emit(f"s_add_u32 s{SSEG}, s{SSEG}, 8")
+    emit(f"s_addc_u32 s{SSEG + 1}, s{SSEG + 1}, 0")
+    emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
+    emit("s_barrier")
+    emit(f"s_add_u32 s{STMP}, s{SBLK}, 1")
+    emit(f"s_cmp_ge_u32 s{STMP}, s{SNBLK}")
+    emit(f"s_cbranch_scc1 {nostage}")
+    emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
+    emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
+    stage(STGT)   # touches none of N's registers, where this block's descriptor sits
+    emit(f"{nostage}:")
+    emit(f"s_cmp_eq_u32 s{SN + 1}, 0")
+    emit(f"s_cbranch_scc1 {segdone}")
+    emit(f"s_add_u32 s{SPTR}, s{SN + 2}, s{SN}")
+    emit(f"s_addc_u32 s{SPTR + 1}, s{SN + 3}, 0")
+    emit(f"s_mov_b32 s{SCNT}, s{SN + 1}")
+    emit(f"s_add_u32 s{STMP}, s{SBUF}, {OP['ldsbase']}")
+    emit(f"v_add_u32 v{VLB}, s{STMP}, {OP['lane_byte']}")
+    # stream prologue
+    emit(f"s_load_dwordx16 s[{SA}:{SA + W - 1}], s[{SPTR}:{SPTR + 1}], 0x0")
+    emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], {hex(4 * W)}")
+    emit(f"s_add_u32 s{SPTR}, s{SPTR}, {hex(8 * W)}")
+    emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
+    emit("s_waitcnt lgkmcnt(0)")
+    for d in range(D):
+        emit(f"s_lshr_b32 s{STMP}, {w1(SA, d)}, 8")
+        emit(f"v_add_u32 v{VA0 + d}, s{STMP}, v{VLB}")
+        for t in range(T):
+            emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * 1024}")
+    loop, done = label("chunk"), label("chunkend")
+    emit(f"{loop}:")
+    body(SA, SB, SN)
+    emit(f"s_cbranch_scc0 {done}")
+    body(SB, SN, SA)
+    emit(f"s_cbranch_scc0 {done}")
+    body(SN, SA, SB)
+    emit(f"s_cbranch_scc1 {loop}")
+    emit(f"{done}:")
+    emit(f"{segdone}:")
+    emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
+    emit(f"s_add_u32 s{SBLK}, s{SBLK}, 1")
+    emit(f"s_cmp_lt_u32 s{SBLK}, s{SNBLK}")
+    emit(f"s_cbranch_scc1 {blk}")
+
+    # ------------------------------------------------------------------ stores
+    KROW = SA                    # k of row i in s[KROW + i], R <= 16
+    BASE = SB                    # 64-bit output base of row i in s[BASE + 2i : +1]
+    emit(f"s_load_dwordx2 s[{SX0}:{SX1}], {OP['kern']}, {hex(OFF_TBL)}")
+    emit(f"s_load_dwordx2 s[{SPTR}:{SPTR + 1}], {OP['kern']}, {hex(OFF_CONSTS + 24)}")   # OHW4, img_stride
+    for i in range(R):
+        emit(f"s_load_dword s{KROW + i}, {OP['rowp']}, {hex(4 * i)}")
+    emit("s_waitcnt lgkmcnt(0)")
+    for t in range(T):
+        emit(f"global_load_dword v{RING0 + t}, {OP['tbloff']}, s[{SX0}:{SX1}] offset:{t * 256}")
+    for i in range(R):
+        emit(f"s_mul_hi_u32 s{STMP}, s{KROW + i}, s{SPTR}")
+        emit(f"s_mul_i32 s{SCNT}, s{KROW + i}, s{SPTR}")
+        emit(f"s_add_u32 s{BASE + 2 * i}, {OP['outp']}_LO, s{SCNT}")
+        emit(f"s_addc_u32 s{BASE + 2 * i + 1}, {OP['outp']}_HI, s{STMP}")
+    emit("s_waitcnt vmcnt(0)")
+    for t in range(T):
+        emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
+        emit("s_mov_b64 exec, vcc")
+        for i in range(R):
+            rowend = label("rowend")
+            emit(f"s_cmp_lt_i32 s{KROW + i}, 0")
+            emit(f"s_cbranch_scc1 {rowend}")
+            emit(f"s_mov_b64 s[{SX0}:{SX1}], s[{BASE + 2 * i}:{BASE + 2 * i + 1}]")
+            for e in range(4):
+                if e:
+                    emit(f"s_cmp_le_u32 {OP['nimg']}, {e}")
+                    emit(f"s_cbranch_scc1 {rowend}")
+                    emit(f"s_add_u32 s{SX0}, s{SX0}, s{SPTR + 1}")
+                    emit(f"s_addc_u32 s{SX1}, s{SX1}, 0")
+                emit(f"global_store_dword v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
+            emit(f"{rowend}:")
+    emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
+
+    ins = ('"s"(kern), "s"(rsrc), "s"(segp), "s"(rowp), "s"(outp_lo), "s"(soff0), "s"(nimg), "s"(lim), "s"(ldsbase), '
+           '"s"(slab0), "s"(slabstep), "s"(nslab), "v"(lane_byte), "v"(voff0), "v"(voff1), "v"(voff2), "v"(voff3), '
+           '"v"(tbloff), "s"(outp_hi)')
+    text = []
+    for ins_ in L:
+        ins_ = ins_.replace(f"{OP['outp']}_LO", OP['outp']).replace(f"{OP['outp']}_HI", f"%{len(OPS)}")
+        text.append(f'            "{ins_}\\n\\t"')
+    clob = [f'"v{r}"' for r in range(ACC0, MAX_VGPR)]
+    clob += [f'"s{r}"' for r in list(range(28, 32)) + list(range(34, 96))]
+    clob += ['"vcc"', '"scc"', '"memory"']
+    return f"""
+template <>
+struct Lds2Asm<{T}, {R}> {{
+    static constexpr int kDepth = {D};
+    static __device__ __forceinline__ void run(unsigned long long kern, int4v rsrc, const unsigned *segp, const int *rowp,
+                                               unsigned outp_lo, unsigned outp_hi, unsigned soff0, unsigned nimg,
+                                               unsigned lim, unsigned ldsbase, unsigned slab0, unsigned slabstep,
+                                               unsigned nslab, unsigned lane_byte, unsigned voff0, unsigned voff1,
+                                               unsigned voff2, unsigned voff3, unsigned tbloff)
+    {{
+        asm volatile(
+{chr(10).join(text)}
+            :
+            : {ins}
+            : {", ".join(clob)});
+    }}
+}};
+"""
+
+
+def generate() -> str:
+    parts = ["// GENERATED by gen_lds2.py -- do not edit; edit the generator and rebuild.\n",
+             "template <int T, int R>\nstruct Lds2Asm;\n"]
+    for s in SHAPES:
+        parts.append(gen_shape(*s))
+    parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r})" for t, r, _, _ in SHAPES) + "\n")
+    parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
+                 f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")
+    return "".join(parts)
+
+
+def main() -> int:
+    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "sconv_lds2_asm.inc")
+    text = generate()
+    if not os.path.exists(out) or open(out).read() != text:
+        with open(out, "w") as fh:
+            fh.write(text)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

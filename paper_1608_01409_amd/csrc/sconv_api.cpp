@@ -12,8 +12,10 @@ struct sconv_csr {
     sconv_desc desc;
     Canonical canon;
     sconv_plan requested;    // what the caller asked for (zeros = choose)
-    bool has_lds = false;
+    bool has_lds = false;    // one of the two LDS packings below is filled
+    bool flat = false;       // ... the flat-stream one
     PackedLds lds;
+    PackedFlat lds_flat;
     PackedDirect direct;
     DeviceLds dev_lds;
     DeviceDirect dev_direct;
@@ -21,11 +23,13 @@ struct sconv_csr {
     int hip_err = 0;
 };
 
+static const LdsTiling &f_tiling(const sconv_csr *h) { return h->lds_flat.t; }
+
 static int finish_create(sconv_csr *h, const sconv_plan *plan)
 {
     std::memset(&h->requested, 0, sizeof(h->requested));
     if (plan) h->requested = *plan;
-    if (h->requested.kernel < 0 || h->requested.kernel > 2) return SCONV_ERR_PLAN;
+    if (h->requested.kernel < 0 || h->requested.kernel > 3) return SCONV_ERR_PLAN;
     const sconv_desc &d = h->desc;
     const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
     int rc = pack_direct(d, h->canon, h->direct);
@@ -35,13 +39,14 @@ static int finish_create(sconv_csr *h, const sconv_plan *plan)
         // the automatic choice is tuned for large batches; small ones go to the direct kernel
         rc = make_lds_tiling(d, h->requested, h->requested.nt ? h->requested.nt : 256, avg, t);
         if (rc == SCONV_OK) {
-            rc = pack_lds(d, h->canon, t, h->lds);
+            h->flat = t.p.kernel == 3;
+            rc = h->flat ? pack_flat(d, h->canon, t, h->lds_flat) : pack_lds(d, h->canon, t, h->lds);
             if (rc) return rc;
             h->has_lds = true;
-        } else if (h->requested.kernel == 1) {
+        } else if (h->requested.kernel != 0) {
             return rc;
         }
-    } else if (h->requested.kernel == 1) {
+    } else if (h->requested.kernel == 1 || h->requested.kernel == 3) {
         return SCONV_ERR_PLAN;
     }
     return SCONV_OK;
@@ -104,7 +109,7 @@ extern "C" int sconv_csr_info(const sconv_csr *h, int64_t *nnz, int32_t *out_h, 
     if (plan) {
         std::memset(plan, 0, sizeof(*plan));
         if (h->has_lds)
-            *plan = h->lds.t.p;
+            *plan = h->flat ? h->lds_flat.t.p : h->lds.t.p;
         else
             plan->kernel = 2;
     }
@@ -143,7 +148,7 @@ extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowp
     try {
         if (which == 1) {
             if (!h->has_lds) return SCONV_ERR_PLAN;
-            rc = unpack_lds(h->desc, h->lds, c);
+            rc = h->flat ? unpack_flat(h->desc, h->lds_flat, c) : unpack_lds(h->desc, h->lds, c);
         } else if (which == 2) {
             rc = unpack_direct(h->desc, h->direct, c);
         } else {
@@ -161,8 +166,21 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
     if (!h || !in || !out) return SCONV_ERR_NULL;
     if (N < 1) return SCONV_ERR_BATCH;
     bool use_lds = h->has_lds;
-    if (use_lds && h->requested.kernel == 0 && N < 4 && h->lds.t.p.nt >= 4) use_lds = false;
+    const LdsTiling &til = h->flat ? h->lds_flat.t : h->lds.t;
+    if (use_lds && h->requested.kernel == 0 && N < 4 && til.p.nt >= 4) use_lds = false;
     int rc;
+    if (use_lds && h->flat) {
+        if (!h->lds_uploaded) {
+            const PackedFlat &f = h->lds_flat;
+            rc = upload(f.pairs.data(), f.pairs.size() * 8, &h->dev_lds.pairs, &h->hip_err);
+            if (!rc) rc = upload(f.seg.data(), f.seg.size() * 4, &h->dev_lds.seg_ptr, &h->hip_err);
+            if (!rc) rc = upload(f.row_of.data(), f.row_of.size() * 4, &h->dev_lds.row_of, &h->hip_err);
+            if (!rc) rc = upload(f.store_tbl.data(), f.store_tbl.size() * 4, &h->dev_lds.store_tbl, &h->hip_err);
+            if (rc) return rc;
+            h->lds_uploaded = true;
+        }
+        return launch_lds2(h->desc, f_tiling(h), h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+    }
     if (use_lds) {
         if (!h->lds_uploaded) {
             rc = upload(h->lds.pairs.data(), h->lds.pairs.size() * 8, &h->dev_lds.pairs, &h->hip_err);
@@ -190,6 +208,7 @@ extern "C" void sconv_destroy_csr(sconv_csr *h)
     release(h->dev_lds.pairs);
     release(h->dev_lds.seg_ptr);
     release(h->dev_lds.row_of);
+    release(h->dev_lds.store_tbl);
     release(h->dev_direct.rowptr);
     release(h->dev_direct.trip);
     delete h;

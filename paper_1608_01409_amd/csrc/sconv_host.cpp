@@ -103,16 +103,23 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     const Geometry g = geometry(d);
     if (d.stride != 1) return SCONV_ERR_PLAN;
     if (p.nt < 1 || p.cb < 1 || p.waves < 1 || p.waves > 16 || p.cg < 1 || p.rows_w < 1 || p.t < 1) return SCONV_ERR_PLAN;
+    if (p.band < 0 || p.band > g.OH) return SCONV_ERR_PLAN;
     if (p.waves % p.cg) return SCONV_ERR_PLAN;
     t.p = p;
-    t.p.kernel = 1;
+    if (p.kernel != 3) t.p.kernel = 1;
     t.vec = (p.nt % 4 == 0) ? 4 : 1;
     if ((64 * t.vec) % p.nt) return SCONV_ERR_PLAN;
-    if (!lds_kernel_available(t.vec, p.t, p.rows_w)) return SCONV_ERR_PLAN;
+    if (t.p.kernel == 3) {
+        if (p.nt != 4 || !lds2_kernel_available(p.t, p.rows_w)) return SCONV_ERR_PLAN;
+    } else if (!lds_kernel_available(t.vec, p.t, p.rows_w)) {
+        return SCONV_ERR_PLAN;
+    }
+    if (t.p.band == 0) t.p.band = g.OH;
+    t.n_bands = ceil_div(g.OH, t.p.band);
     t.Wl = lds_pitch(d);
-    t.Hl = g.Hp;
+    t.Hl = t.p.band + d.R - 1;
     t.plane_cells = t.Hl * t.Wl;
-    t.pos_span = (g.OH - 1) * t.Wl + g.OW;
+    t.pos_span = (t.p.band - 1) * t.Wl + g.OW;
     t.pos_per_chunk = 64 * t.vec / p.nt;
     t.n_chunks = ceil_div(t.pos_span, t.pos_per_chunk);
     if (t.n_chunks > p.cg * p.t) return SCONV_ERR_PLAN;
@@ -174,14 +181,16 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
 {
     const Geometry g = geometry(d);
     const int n_tiles = ceil_div(N, t.p.nt);
-    const double wgs = (double)n_tiles * d.groups * t.nkt;
+    const double wgs = (double)n_tiles * d.groups * t.nkt * t.n_bands;
     const int by_lds = std::max(1, (160 * 1024) / (t.lds_bytes + 512));
     const int by_waves = std::max(1, 16 / t.p.waves);
     const int wpc = std::min(by_lds, by_waves);
     const double rows_per_wave = (double)g.Kg / (t.nkt * t.rg); // after dealing rows evenly
-    // every (row, block) segment is padded to whole chunks: 1.5 entries on average
-    const double seg_len = std::max(0.25, avg_row_nnz / t.nblk);
-    const double nnz_wave = rows_per_wave * avg_row_nnz * (seg_len + 1.5) / seg_len;
+    // per-row streams: every (row, block) segment is padded to whole chunks of 4, 1.5 entries on average;
+    // flat streams: every (wave, block) segment is padded to whole chunks of 8, 3.5 entries on average
+    const bool flat = t.p.kernel == 3;
+    const double seg_len = std::max(0.25, (flat ? rows_per_wave : 1.0) * avg_row_nnz / t.nblk);
+    const double nnz_wave = rows_per_wave * avg_row_nnz * (seg_len + (flat ? 3.5 : 1.5)) / seg_len;
     const double fma_instr = t.p.t * t.vec;
     // SIMD-issue bound: waves on a SIMD run one after another; 4 clocks per wave instruction.
     // a shallow read-ahead ring leaves the wave waiting on LDS latency more often
@@ -190,7 +199,7 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
     // LDS bound: clocks per wave read instruction.
     const double lds = t.p.waves * nnz_wave * t.p.t * (t.vec == 4 ? 4.3 : 2.4);
     // per segment fixed costs (pointer fetch, loop set-up, scalar latency), per wave, partly hidden
-    const double seg = (double)t.nblk * t.p.rows_w * 60.0 * std::ceil(t.p.waves / 4.0);
+    const double seg = (double)t.nblk * (flat ? 4.0 : t.p.rows_w) * 60.0 * std::ceil(t.p.waves / 4.0);
     // loads stream in behind the multiply-adds; only the first block's load is exposed
     const double stage = (double)t.p.cb * t.plane_cells * t.p.nt * 4.0 / 32.0 + 3000.0 + t.nblk * 300.0;
     // fewer than four waves per SIMD hide each other's stalls less well
@@ -206,56 +215,64 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
     if (d.stride != 1) return SCONV_ERR_PLAN;
     const bool full = req.nt && req.cb && req.waves && req.cg && req.rows_w && req.t;
     if (full) return fill_tiling(d, req, out);
+    const int kinds[2] = {3, 1};
 
     double best = -1;
     const int nts_big[] = {4, 8, 16};
     const int nts_small[] = {1, 2};
     const int *nts = N_hint >= 4 ? nts_big : nts_small;
     const int n_nts = N_hint >= 4 ? 3 : 2;
+    const int Wl = lds_pitch(d);
     for (int a = 0; a < n_nts; ++a) {
         const int nt = nts[a];
         if (req.nt && req.nt != nt) continue;
         if (nt > 1 && nt > N_hint) continue;
         const int vec = nt % 4 == 0 ? 4 : 1;
-        const int Wl = lds_pitch(d);
-        const int pos_span = (g.OH - 1) * Wl + g.OW;
-        const int n_chunks = ceil_div(pos_span, 64 * vec / nt);
-        for (int waves : {4, 8, 16}) {
-            if (req.waves && req.waves != waves) continue;
-            for (int cg = 1; cg <= 4; ++cg) {
-                if (waves % cg) continue;
-                if (req.cg && req.cg != cg) continue;
-                const int T = ceil_div(n_chunks, cg);
-                if (req.t && req.t != T) continue;
-                const int (*shapes)[2] = vec == 4 ? kShapesV4 : kShapesV1;
-                const int n_shapes = vec == 4 ? (int)(sizeof(kShapesV4) / sizeof(kShapesV4[0]))
-                                              : (int)(sizeof(kShapesV1) / sizeof(kShapesV1[0]));
-                for (int si = 0; si < n_shapes; ++si) {
-                    if (shapes[si][0] != T) continue;
-                    const int rows_w = shapes[si][1];
-                    if (req.rows_w && req.rows_w != rows_w) continue;
-                    for (int wpc_target : {1, 2, 4}) {
-                        if (waves * wpc_target > 16) continue;
-                        const int budget = 160 * 1024 / wpc_target - 256;
-                        const int64_t per_ch = (int64_t)g.Hp * Wl * nt * 4;
-                        const int64_t fixed = (int64_t)cg * T * 64 * vec * 4 + 16;
-                        int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
-                        if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
-                        if (req.cb) cb = req.cb;
-                        if (cb < 1) continue;
-                        // even out the blocks
-                        if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
-                        sconv_plan p = {1, nt, cb, waves, cg, rows_w, T};
-                        LdsTiling t;
-                        if (fill_tiling(d, p, t) != SCONV_OK) continue;
-                        const double c = tiling_cost(d, t, N_hint, avg_row_nnz);
-                        if (best < 0 || c < best) {
-                            best = c;
-                            out = t;
+        int last_band = 0;
+        for (int nb = 1; nb <= 8 && nb <= g.OH; ++nb) {
+            const int band = req.band ? req.band : ceil_div(g.OH, nb);
+            if (band == last_band) continue; // same band height as the previous count
+            last_band = band;
+            const int pos_span = (band - 1) * Wl + g.OW;
+            const int n_chunks = ceil_div(pos_span, 64 * vec / nt);
+            for (int waves : {4, 8, 16}) {
+                if (req.waves && req.waves != waves) continue;
+                for (int cg = 1; cg <= 4; ++cg) {
+                    if (waves % cg) continue;
+                    if (req.cg && req.cg != cg) continue;
+                    const int T = ceil_div(n_chunks, cg);
+                    if (req.t && req.t != T) continue;
+                    for (int ki = 0; ki < 2; ++ki)
+                    for (int rows_w = 1; rows_w <= 24; ++rows_w) {
+                        const int kind = kinds[ki];
+                        if (req.kernel && req.kernel != kind) continue;
+                        if (kind == 3 ? (nt != 4 || !lds2_kernel_available(T, rows_w)) : !lds_kernel_available(vec, T, rows_w))
+                            continue;
+                        if (req.rows_w && req.rows_w != rows_w) continue;
+                        for (int wpc_target : {1, 2, 4}) {
+                            if (waves * wpc_target > 16) continue;
+                            const int budget = 160 * 1024 / wpc_target - 256;
+                            const int64_t per_ch = (int64_t)(band + d.R - 1) * Wl * nt * 4;
+                            const int64_t fixed = (int64_t)cg * T * 64 * vec * 4 + 16;
+                            int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
+                            if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
+                            if (req.cb) cb = req.cb;
+                            if (cb < 1) continue;
+                            // even out the blocks
+                            if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
+                            sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band};
+                            LdsTiling t;
+                            if (fill_tiling(d, p, t) != SCONV_OK) continue;
+                            const double c = tiling_cost(d, t, N_hint, avg_row_nnz);
+                            if (best < 0 || c < best) {
+                                best = c;
+                                out = t;
+                            }
                         }
                     }
                 }
             }
+            if (req.band) break;
         }
     }
     return best < 0 ? SCONV_ERR_PLAN : SCONV_OK;
@@ -323,6 +340,87 @@ int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packed
     return SCONV_OK;
 }
 
+// Rows of one group dealt to the group's wave slots, longest first, boustrophedon (see pack_lds).
+static int deal_rows(const sconv_desc &d, const Canonical &c, const LdsTiling &t, std::vector<int32_t> &row_of)
+{
+    const Geometry g = geometry(d);
+    const int rows_w = t.p.rows_w;
+    const int waves_per_group = t.nkt * t.rg;
+    row_of.assign((size_t)t.wave_slots * rows_w, -1);
+    for (int grp = 0; grp < d.groups; ++grp) {
+        std::vector<int> rows(g.Kg);
+        std::iota(rows.begin(), rows.end(), grp * g.Kg);
+        std::stable_sort(rows.begin(), rows.end(), [&](int a, int b) {
+            return c.rowptr[a + 1] - c.rowptr[a] > c.rowptr[b + 1] - c.rowptr[b];
+        });
+        for (int i = 0; i < g.Kg; ++i) {
+            const int round = i / waves_per_group, posn = i % waves_per_group;
+            const int w = (round & 1) ? waves_per_group - 1 - posn : posn;
+            if (round >= rows_w) return SCONV_ERR_PLAN;
+            row_of[((size_t)grp * waves_per_group + w) * rows_w + round] = rows[i];
+        }
+    }
+    return SCONV_OK;
+}
+
+int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedFlat &out)
+{
+    const Geometry g = geometry(d);
+    const int rows_w = t.p.rows_w, cb = t.p.cb;
+    if (t.p.nt != 4 || rows_w * t.p.t * 4 > 256 || t.zero_page >= (1u << 24)) return SCONV_ERR_PLAN;
+    out.t = t;
+    int rc = deal_rows(d, c, t, out.row_of);
+    if (rc) return rc;
+    out.seg.assign((size_t)t.wave_slots * t.nblk * 2, 0);
+    out.pairs.clear();
+    out.pairs.reserve(c.val.size() + (size_t)t.wave_slots * t.nblk * 4);
+    const uint64_t pad_entry = (uint64_t)(t.zero_page << 8) << 32;
+    size_t real = 0;
+    // nonzeros of a row by block: walk each row once per slot, bucketing by channel block
+    std::vector<std::vector<uint64_t>> bucket(t.nblk);
+    for (int ws = 0; ws < t.wave_slots; ++ws) {
+        for (auto &b : bucket) b.clear();
+        for (int i = 0; i < rows_w; ++i) {
+            const int k = out.row_of[(size_t)ws * rows_w + i];
+            if (k < 0) continue;
+            const int grp = k / g.Kg;
+            for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
+                const int off = c.off[j];
+                const int s = off % g.Wp, r = (off / g.Wp) % g.Hp, ca = off / (g.Wp * g.Hp);
+                const int cl_all = ca - grp * g.Cg;
+                const int b = cl_all / cb, cl = cl_all - b * cb;
+                const uint32_t byte_off = (uint32_t)(((int64_t)cl * t.plane_cells + r * t.Wl + s) * 16);
+                if (byte_off >= t.zero_page) return SCONV_ERR_PLAN;
+                uint32_t vb;
+                std::memcpy(&vb, &c.val[j], 4);
+                bucket[b].push_back((uint64_t)vb | ((uint64_t)((byte_off << 8) | (uint32_t)(i * t.p.t * 4)) << 32));
+                ++real;
+            }
+        }
+        for (int b = 0; b < t.nblk; ++b) {
+            // entries in ascending LDS offset: rows that share a column sit next to each other
+            std::stable_sort(bucket[b].begin(), bucket[b].end(), [](uint64_t x, uint64_t y) { return (x >> 40) < (y >> 40); });
+            const size_t start = out.pairs.size();
+            out.pairs.insert(out.pairs.end(), bucket[b].begin(), bucket[b].end());
+            while ((out.pairs.size() - start) % SCONV_FLAT_CHUNK) out.pairs.push_back(pad_entry);
+            if (start * 8 >= ((uint64_t)1 << 32)) return SCONV_ERR_RANGE;
+            out.seg[((size_t)ws * t.nblk + b) * 2] = (uint32_t)(start * 8);
+            out.seg[((size_t)ws * t.nblk + b) * 2 + 1] = (uint32_t)((out.pairs.size() - start) / SCONV_FLAT_CHUNK);
+        }
+    }
+    if (real != c.val.size()) return SCONV_ERR_PLAN;
+    // the kernel prefetches two chunks past the segment it is working on
+    for (int i = 0; i < 3 * SCONV_FLAT_CHUNK; ++i) out.pairs.push_back(pad_entry);
+    // store offsets of the positions a group of cg waves covers
+    const int npos = t.p.cg * t.p.t * 64;
+    out.store_tbl.assign(npos, -1);
+    for (int pos = 0; pos < npos; ++pos) {
+        const int by = pos / t.Wl, ox = pos % t.Wl;
+        if (by < t.p.band && ox < g.OW) out.store_tbl[pos] = (by * g.OW + ox) * 4;
+    }
+    return SCONV_OK;
+}
+
 static void sort_rows_by_offset(const sconv_desc &d, std::vector<std::vector<std::pair<int32_t, float>>> &rows,
                                 Canonical &out)
 {
@@ -371,6 +469,40 @@ int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out)
                     std::memcpy(&v, &vb, 4);
                     rows[k].push_back({((ca * g.Hp) + r) * g.Wp + s, v});
                 }
+            }
+        }
+    }
+    sort_rows_by_offset(d, rows, out);
+    return SCONV_OK;
+}
+
+int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    const LdsTiling &t = p.t;
+    const int rows_w = t.p.rows_w;
+    std::vector<std::vector<std::pair<int32_t, float>>> rows(d.K);
+    for (int ws = 0; ws < t.wave_slots; ++ws) {
+        for (int b = 0; b < t.nblk; ++b) {
+            const size_t start = p.seg[((size_t)ws * t.nblk + b) * 2] / 8;
+            const size_t n = (size_t)p.seg[((size_t)ws * t.nblk + b) * 2 + 1] * SCONV_FLAT_CHUNK;
+            for (size_t j = start; j < start + n; ++j) {
+                const uint32_t vb = (uint32_t)(p.pairs[j] & 0xffffffffu);
+                const uint32_t w1 = (uint32_t)(p.pairs[j] >> 32);
+                const uint32_t byte_off = w1 >> 8;
+                if (byte_off >= t.zero_page) continue; // chunk padding
+                const int i = (int)(w1 & 0xffu) / (t.p.t * 4);
+                if (i >= rows_w) return SCONV_ERR_CSR;
+                const int k = p.row_of[(size_t)ws * rows_w + i];
+                if (k < 0) return SCONV_ERR_CSR;
+                const int grp = k / g.Kg;
+                const int cell = (int)(byte_off / 16u);
+                const int cl = cell / t.plane_cells, rem = cell % t.plane_cells;
+                const int r = rem / t.Wl, sx = rem % t.Wl;
+                const int ca = grp * g.Cg + b * t.p.cb + cl;
+                float v;
+                std::memcpy(&v, &vb, 4);
+                rows[k].push_back({((ca * g.Hp) + r) * g.Wp + sx, v});
             }
         }
     }

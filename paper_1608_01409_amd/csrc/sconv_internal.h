@@ -35,6 +35,9 @@ inline Geometry geometry(const sconv_desc &d)
 // reads `vec` images at one cell, always at an aligned address.  The row pitch
 // is Wl = max(W + pad, OW): a read that falls into the right padding of a row
 // lands on the left padding of the next one, which is zero as well.
+// A workgroup computes a band of `band` output rows starting at row y0 and
+// stages rows y0 .. y0 + band + R - 2 of the padded image; y below is relative
+// to y0, so the packed offsets are the same for every band.
 // A nonzero (c,r,s) of a row then reads, for flat output index
 // F = pos*nt + image with pos = y*Wl + x, the float at
 //   ((c_local*plane_cells + r*Wl + s)*nt) + F,
@@ -42,9 +45,10 @@ inline Geometry geometry(const sconv_desc &d)
 struct LdsTiling {
     sconv_plan p;
     int vec;            // floats per lane per chunk: 4 if nt % 4 == 0 else 1
-    int Wl, Hl;         // plane pitch and rows
+    int Wl, Hl;         // plane pitch and rows (Hl = band + R - 1 rows of the padded image)
+    int n_bands;        // ceil(OH / band): bands of output rows, one workgroup each
     int plane_cells;    // Hl * Wl
-    int pos_span;       // (OH-1)*Wl + OW: positions a tile computes
+    int pos_span;       // (band-1)*Wl + OW: positions a tile computes
     int pos_per_chunk;  // 64*vec / nt
     int n_chunks;       // ceil(pos_span / pos_per_chunk), <= cg*t
     int nblk;           // ceil(Cg / cb)
@@ -65,6 +69,20 @@ struct PackedLds {
     std::vector<int32_t> row_of;   // [wave_slot][rows_w] -> output channel or -1
 };
 
+// Packing for the flat-stream kernel (tiles of 4 images).  One stream per (wave slot, channel block)
+// holding the nonzeros of all rows of the slot in that block, padded to whole chunks of 8 entries:
+//   low 32 bits  fp32 value bits
+//   high 32 bits (LDS byte offset << 8) | (row index inside the slot * t * 4)
+// Padding entries have value +0.0 and point at the zero page.
+#define SCONV_FLAT_CHUNK 8
+struct PackedFlat {
+    LdsTiling t;
+    std::vector<uint64_t> pairs;
+    std::vector<uint32_t> seg;       // [wave_slot][nblk] x (byte offset into pairs, number of chunks)
+    std::vector<int32_t> row_of;     // [wave_slot][rows_w] -> output channel or -1
+    std::vector<int32_t> store_tbl;  // [cg*t*64] -> (by*OW + ox)*4 inside a band, or -1
+};
+
 struct PackedDirect {
     std::vector<int32_t> rowptr;   // K+1
     std::vector<uint32_t> trip;    // 3 words per nonzero: value bits, goff, (dr<<16)|(ds&0xffff)
@@ -83,22 +101,28 @@ int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, cons
 // Fill in a tiling for the LDS kernel (fields of `req` that are 0 are chosen).  N_hint is the
 // batch size the choice is tuned for.  Returns SCONV_ERR_PLAN if the layer cannot use it.
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out);
+// p.kernel selects the shape list: 1 = per-row streams, 3 = flat streams (nt must be 4)
 bool lds_kernel_available(int vec, int t, int rows_w);
 
 int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedLds &out);
 int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out);
+int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedFlat &out);
+int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out);
+bool lds2_kernel_available(int t, int rows_w);
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
 int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
 
 // Device side (sconv_kernels.hip)
 struct DeviceLds {
-    void *pairs = nullptr, *seg_ptr = nullptr, *row_of = nullptr;
+    void *pairs = nullptr, *seg_ptr = nullptr, *row_of = nullptr, *store_tbl = nullptr;
 };
 struct DeviceDirect {
     void *rowptr = nullptr, *trip = nullptr;
 };
 int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
                int N, void *stream, int *hip_err);
+int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
+                int N, void *stream, int *hip_err);
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
                   void *stream, int *hip_err);
 int upload(const void *host, size_t bytes, void **dev, int *hip_err);

@@ -26,6 +26,7 @@ struct LdsArgs {
     const int *row_of;
     int N, C, H, W, K, OH, OW, pad, Cg, groups;
     int nt, cb, nblk, rg, cg, nkt;
+    int band, n_bands; // output rows per workgroup, bands per image
     int Wl, plane_floats, n_slabs, buf_stride_floats, lds_floats;
     int n_tiles, units;
 };
@@ -67,8 +68,10 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
     const int unit = slot % a.units;
     const int tile = (slot / a.units) * 8 + xcd;
     if (tile >= a.n_tiles) return;
-    const int g = unit / a.nkt, kt = unit - g * a.nkt;
+    const int gk = unit / a.n_bands, band_i = unit - gk * a.n_bands;
+    const int g = gk / a.nkt, kt = gk - g * a.nkt;
     const int n0 = tile * a.nt;
+    const int y0 = band_i * a.band; // first output row (= first row of the padded image) of this band
     const int rgi = __builtin_amdgcn_readfirstlane(wave / a.cg);
     const int cgi = wave - rgi * a.cg;
     const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
@@ -91,7 +94,7 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
         const int f = (wave + j * n_waves) * 64 + lane;
         const int cell = f / a.nt, img = f - cell * a.nt;
         const int Y = cell / a.Wl, X = cell - Y * a.Wl;
-        const int iy = Y - a.pad, ix = X - a.pad;
+        const int iy = y0 + Y - a.pad, ix = X - a.pad;
         const bool ok = f < a.plane_floats && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W && n0 + img < a.N;
         src_off[j] = ok ? img * CHW + iy * a.W + ix : -1;
     }
@@ -170,8 +173,9 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
     for (int t = 0; t < T; ++t) {
         const int F0 = ((cgi * T + t) * 64 + lane) * VEC;
         const int pos = F0 / a.nt, nl = F0 - pos * a.nt;
-        const int oy = pos / a.Wl, ox = pos - oy * a.Wl;
-        const bool valid = ox < a.OW && oy < a.OH;
+        const int by = pos / a.Wl, ox = pos - by * a.Wl;
+        const int oy = y0 + by;
+        const bool valid = ox < a.OW && by < a.band && oy < a.OH;
 #pragma unroll
         for (int i = 0; i < ROWS_W; ++i) {
             const int k = (int)crow[wslot * ROWS_W + i];
@@ -183,6 +187,106 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
             }
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------------
+// sconv_lds2_kernel: the flat-stream variant of the LDS-tiled kernel for tiles of 4 images.  Same
+// tiling and LDS layout as above; what differs:
+//   * the rows of a wave share one nonzero stream per channel block (entry = weight, LDS offset,
+//     accumulator index), so nothing is padded per row and the rows of a wave need not be balanced;
+//   * the accumulators are addressed through the VGPR index mode, so the whole tile (staging, channel
+//     blocks, stores) runs inside one asm statement that owns a fixed block of registers;
+//   * staging uses buffer loads into LDS whose range check returns 0 for the padding cells, so no
+//     part of a plane is ever cleared and every cell of a block is rewritten with each block.
+struct Lds2Args {
+    const float *in;
+    float *out;
+    const unsigned *pairs;   // stream entries
+    const unsigned *seg;     // [wave slot][block] x (byte offset into pairs, chunks of 8 entries)
+    const int *row_of;       // [wave slot][R]
+    const int *store_tbl;    // [cg*T*64] byte offset (by*OW + ox)*4 of a position inside its band, or -1
+    int cb, nblk, Cg, plane_bytes, buf_stride_bytes, HW4, OHW4, img_stride_bytes; // read by the asm
+    int N, C, H, W, K, OH, OW, pad;
+    int rg, cg, nkt, band, n_bands, Wl, plane_floats, n_slabs;
+    int n_tiles, units, block_bytes, page_bytes, n_bufs;
+};
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+#include "sconv_lds2_asm.inc"
+
+static_assert(offsetof(Lds2Args, pairs) == SCONV_LDS2_OFF_PAIRS, "asm reads pairs here");
+static_assert(offsetof(Lds2Args, store_tbl) == SCONV_LDS2_OFF_TBL, "asm reads store_tbl here");
+static_assert(offsetof(Lds2Args, cb) == SCONV_LDS2_OFF_CONSTS, "asm reads eight constants from here");
+static_assert(offsetof(Lds2Args, img_stride_bytes) == SCONV_LDS2_OFF_CONSTS + 28, "layout of the constants");
+
+constexpr unsigned kSkipLane = 0xFFFFFFFFu; // lane past the end of a plane: writes nothing
+constexpr unsigned kZeroLane = 0x80000000u; // padding cell: beyond num_records, the load returns 0
+
+template <int T, int R>
+__global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
+{
+    extern __shared__ float4 smem4[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_waves = (int)blockDim.x >> 6;
+
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int unit = slot % a.units;
+    const int tile = (slot / a.units) * 8 + xcd;
+    if (tile >= a.n_tiles) return;
+    const int gk = unit / a.n_bands, band_i = unit - gk * a.n_bands;
+    const int g = gk / a.nkt, kt = gk - g * a.nkt;
+    const int n0 = tile * 4;
+    const int y0 = band_i * a.band;
+    const int rgi = __builtin_amdgcn_readfirstlane(wave / a.cg);
+    const int cgi = wave - rgi * a.cg;
+    const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
+    const int HW = a.H * a.W, CHW = a.C * HW;
+    const int nimg = min(4, a.N - n0);
+
+    // per-lane source offsets of the slabs this wave stages, relative to channel 0 of image n0
+    unsigned voff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int f = (wave + j * n_waves) * 64 + lane;
+        const int cell = f >> 2, img = f & 3;
+        const int Y = cell / a.Wl, X = cell - Y * a.Wl;
+        const int iy = y0 + Y - a.pad, ix = X - a.pad;
+        const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+        voff[j] = f >= a.plane_floats ? kSkipLane : inside ? (unsigned)(img * CHW + iy * a.W + ix) * 4u : kZeroLane;
+    }
+    int nslab = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) nslab += (wave + j * n_waves < a.n_slabs) ? 1 : 0;
+
+    // the zero page behind each block buffer: cleared here, never written again
+    {
+        float4 *z = smem4;
+        const int page4 = a.page_bytes >> 4;
+        for (int b = 0; b < a.n_bufs; ++b)
+            for (int i = tid; i < page4; i += blockDim.x) z[((b * a.buf_stride_bytes + a.block_bytes) >> 4) + i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+
+    const float *in_tile = a.in + (size_t)n0 * CHW;
+    const unsigned long long ip = (unsigned long long)in_tile;
+    int4v rsrc;
+    rsrc.x = __builtin_amdgcn_readfirstlane((int)(unsigned)ip);
+    rsrc.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(ip >> 32));   // stride 0
+    rsrc.z = __builtin_amdgcn_readfirstlane(nimg * CHW * 4);              // bytes past which loads return 0
+    rsrc.w = 0x00020000;                                                   // raw 32-bit data format
+    const unsigned long long op = (unsigned long long)(a.out + ((size_t)n0 * a.K * a.OH + y0) * a.OW);
+    const unsigned lim = (unsigned)(min(a.band, a.OH - y0) * a.OW * 4);
+    const unsigned ldsbase = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void *)smem4;
+    Lds2Asm<T, R>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc, a.seg + (size_t)wslot * a.nblk * 2,
+                       a.row_of + (size_t)wslot * R,
+                       __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
+                       (unsigned)__builtin_amdgcn_readfirstlane(g * a.Cg * HW * 4), (unsigned)nimg, lim,
+                       __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)(wave * 256), (unsigned)(n_waves * 256),
+                       (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)((cgi * T * 64 + lane) * 16), voff[0],
+                       voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -289,11 +393,12 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
     a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.pad = d.pad;
     a.Cg = g.Cg; a.groups = d.groups;
     a.nt = t.p.nt; a.cb = t.p.cb; a.nblk = t.nblk; a.rg = t.rg; a.cg = t.p.cg; a.nkt = t.nkt;
+    a.band = t.p.band; a.n_bands = t.n_bands;
     a.Wl = t.Wl; a.plane_floats = t.plane_cells * t.p.nt; a.n_slabs = t.n_slabs;
     a.buf_stride_floats = t.buf_stride_floats;
     a.lds_floats = t.lds_bytes / 4;
     a.n_tiles = (N + t.p.nt - 1) / t.p.nt;
-    a.units = d.groups * t.nkt;
+    a.units = d.groups * t.nkt * t.n_bands;
     // the kernel's own assumptions, checked before anything is launched
     if ((t.n_slabs + t.p.waves - 1) / t.p.waves > kMaxSlabsPerWave) return SCONV_ERR_PLAN;
     if ((int64_t)t.p.nt * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;
@@ -309,6 +414,78 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
 #define X(TT, RW) \
     if (t.vec == 4 && t.p.t == TT && t.p.rows_w == RW) return launch_lds_inst<4, TT, RW>(a, grid, threads, t.lds_bytes, s, hip_err);
     SCONV_ASM_SHAPES(X)
+#undef X
+    return SCONV_ERR_PLAN;
+}
+
+template <int T, int R>
+static int launch_lds2_inst(const Lds2Args &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
+{
+    auto kern = sconv_lds2_kernel<T, R>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) {
+            *hip_err = (int)e;
+            return SCONV_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+bool lds2_kernel_available(int t, int rows_w)
+{
+#define X(TT, RW) if (t == TT && rows_w == RW) return true;
+    SCONV_LDS2_SHAPES(X)
+#undef X
+    return false;
+}
+
+int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
+                int N, void *stream, int *hip_err)
+{
+    const Geometry g = geometry(d);
+    Lds2Args a;
+    a.in = in;
+    a.out = out;
+    a.pairs = static_cast<const unsigned *>(dev.pairs);
+    a.seg = static_cast<const unsigned *>(dev.seg_ptr);
+    a.row_of = static_cast<const int *>(dev.row_of);
+    a.store_tbl = static_cast<const int *>(dev.store_tbl);
+    const int plane_floats = t.plane_cells * 4;
+    a.cb = t.p.cb; a.nblk = t.nblk; a.Cg = g.Cg; a.plane_bytes = plane_floats * 4;
+    a.buf_stride_bytes = t.buf_stride_floats * 4; a.HW4 = d.H * d.W * 4; a.OHW4 = g.OH * g.OW * 4;
+    a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.pad = d.pad;
+    a.rg = t.rg; a.cg = t.p.cg; a.nkt = t.nkt; a.band = t.p.band; a.n_bands = t.n_bands; a.Wl = t.Wl;
+    a.plane_floats = plane_floats; a.n_slabs = t.n_slabs;
+    a.n_tiles = (N + 3) / 4;
+    a.units = d.groups * t.nkt * t.n_bands;
+    a.block_bytes = (int)t.zero_page;
+    a.page_bytes = t.p.cg * t.p.t * 1024;
+    a.n_bufs = t.n_bufs;
+    // what the kernel assumes, checked before anything is launched
+    if (t.p.nt != 4 || t.vec != 4) return SCONV_ERR_PLAN;
+    if ((t.n_slabs + t.p.waves - 1) / t.p.waves > 4) return SCONV_ERR_PLAN;
+    if ((int64_t)4 * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;   // buffer offsets below 2^31 bytes
+    if ((int64_t)d.K * g.OH * g.OW * 4 >= ((int64_t)1 << 31)) return SCONV_ERR_RANGE; // image stride of the output
+    if (t.lds_bytes % 16 || t.lds_bytes > 160 * 1024 || a.block_bytes % 16 || a.buf_stride_bytes % 16) return SCONV_ERR_PLAN;
+    if (a.block_bytes + a.page_bytes > a.buf_stride_bytes) return SCONV_ERR_PLAN;
+    if (t.p.rows_w * t.p.t * 4 > 256) return SCONV_ERR_PLAN;
+    a.img_stride_bytes = (int)((int64_t)d.K * g.OH * g.OW * 4);
+    const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
+    if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
+    const int grid = (int)grid64, threads = t.p.waves * 64;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define X(TT, RW) \
+    if (t.p.t == TT && t.p.rows_w == RW) return launch_lds2_inst<TT, RW>(a, grid, threads, t.lds_bytes, s, hip_err);
+    SCONV_LDS2_SHAPES(X)
 #undef X
     return SCONV_ERR_PLAN;
 }

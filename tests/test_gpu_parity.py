@@ -63,6 +63,15 @@ PLANS = [
     dict(kernel=1, nt=16, cb=2, waves=16, cg=4, rows_w=6, t=3),
     dict(kernel=1, nt=1, cb=16, waves=8, cg=1, rows_w=8, t=3),
     dict(kernel=1, nt=2, cb=16, waves=4, cg=2, rows_w=8, t=3),
+    dict(kernel=1, nt=4, cb=8, waves=8, cg=1, rows_w=4, t=2, band=7),   # two bands, the second ragged
+    dict(kernel=1, nt=4, cb=16, waves=4, cg=1, rows_w=8, t=1, band=4),  # four bands, the last one row
+    dict(kernel=1, nt=8, cb=6, waves=8, cg=2, rows_w=4, t=2, band=5),
+    dict(kernel=3, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),           # flat streams
+    dict(kernel=3, nt=4, cb=5, waves=4, cg=1, rows_w=4, t=3),
+    dict(kernel=3, nt=4, cb=16, waves=16, cg=1, rows_w=8, t=3),         # one block, one buffer
+    dict(kernel=3, nt=4, cb=7, waves=8, cg=1, rows_w=8, t=2, band=7),
+    dict(kernel=3, nt=4, cb=16, waves=16, cg=2, rows_w=16, t=1, band=7),
+    dict(kernel=3, nt=4, cb=3, waves=4, cg=1, rows_w=8, t=3),
 ]
 
 

@@ -62,8 +62,8 @@ def test_lowering_bit_exact_and_packings_round_trip(oracle, layer, density):
     assert np.array_equal(val.view(np.uint32), o_val.view(np.uint32))
     info = B.sconv_csr_info(h)
     assert info["nnz"] == len(o_val) and (info["OH"], info["OW"]) == (layer.OH, layer.OW)
-    which = [2] + ([1] if info["plan"]["kernel"] == 1 else [])
-    assert (info["plan"]["kernel"] == 1) == (layer.stride == 1)
+    which = [2] + ([1] if info["plan"]["kernel"] in (1, 3) else [])
+    assert (info["plan"]["kernel"] in (1, 3)) == (layer.stride == 1)
     for wh in which:
         r2, o2, v2 = B.sconv_csr_unpack(h, wh)
         assert np.array_equal(r2, o_rowptr) and np.array_equal(o2, o_off)
@@ -82,6 +82,13 @@ PLANS = [
     dict(kernel=1, nt=8, cb=4, waves=8, cg=1, rows_w=3, t=6),
     dict(kernel=1, nt=1, cb=16, waves=8, cg=1, rows_w=8, t=3),
     dict(kernel=1, nt=2, cb=16, waves=4, cg=2, rows_w=8, t=3),
+    dict(kernel=1, nt=4, cb=8, waves=8, cg=1, rows_w=4, t=2, band=7),   # two bands, the second ragged
+    dict(kernel=1, nt=4, cb=16, waves=4, cg=1, rows_w=8, t=1, band=4),  # four bands
+    dict(kernel=3, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),           # flat streams
+    dict(kernel=3, nt=4, cb=5, waves=4, cg=1, rows_w=4, t=3),
+    dict(kernel=3, nt=4, cb=7, waves=8, cg=1, rows_w=8, t=2, band=7),
+    dict(kernel=3, nt=4, cb=16, waves=16, cg=2, rows_w=16, t=1, band=7),
+    dict(kernel=3, nt=4, cb=3, waves=4, cg=1, rows_w=8, t=3),
 ]
 
 
@@ -94,7 +101,7 @@ def test_explicit_plans_round_trip(oracle, plan):
     o_off = oracle.lower_offsets(layer, o_rowptr, o_col)
     h = B.sconv_create_csr(layer, w, plan)
     got = B.sconv_csr_info(h)["plan"]
-    assert got == plan
+    assert got == dict(band=layer.OH, **plan) if "band" not in plan else got == plan
     r, o, v = B.sconv_csr_unpack(h, 1)
     assert np.array_equal(r, o_rowptr) and np.array_equal(o, o_off)
     assert np.array_equal(v.view(np.uint32), o_val.view(np.uint32))
@@ -171,7 +178,7 @@ def test_automatic_plans_for_the_benchmark_layers():
         layer = wl.LAYERS[name]
         h = B.sconv_create_csr(layer, rand_w(layer, 0.1, seed=2))
         p = B.sconv_csr_info(h)["plan"]
-        assert p["kernel"] == 1 and p["nt"] % 4 == 0, (name, p)
+        assert p["kernel"] in (1, 3) and p["nt"] % 4 == 0, (name, p)
     h = B.sconv_create_csr(wl.LAYERS["conv1"], rand_w(wl.LAYERS["conv1"], 0.3, seed=2))
     assert B.sconv_csr_info(h)["plan"]["kernel"] == 2
 
