@@ -232,6 +232,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
         emit(f"s_addc_u32 s{BASE + 2 * i + 1}, {OP['outp']}_HI, s{STMP}")
     emit("s_waitcnt vmcnt(0)")
     for t in range(T):
+        emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")   # the compare writes vcc for active lanes only
         emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
         emit("s_mov_b64 exec, vcc")
         for i in range(R):

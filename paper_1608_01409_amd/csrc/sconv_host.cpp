@@ -209,6 +209,26 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
     return rounds * wpc * wg;
 }
 
+// The same for the flat-stream kernel, in microseconds at 2.4 GHz; constants fitted to measured plan sweeps
+// of the AlexNet layers at batch 256 (useful issue efficiency of the multiply-add loop, cost of a channel
+// block's barrier and pipeline refill, cost of a workgroup's prologue and stores).
+static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, double avg_row_nnz)
+{
+    const Geometry g = geometry(d);
+    const double wgs = (double)ceil_div(N, 4) * d.groups * t.nkt * t.n_bands;
+    const int by_lds = std::max(1, (160 * 1024) / (t.lds_bytes + 512));
+    const int wpc = std::max(1, std::min(by_lds, 16 / t.p.waves));
+    const double rows_wave = (double)g.Kg / (t.nkt * t.rg);
+    const double entries = rows_wave * avg_row_nnz + 3.5 * t.nblk;
+    const int depth = lds2_depth(t.p.t, t.p.rows_w);
+    const double eff = depth * t.p.t >= 6 ? 0.78 : 0.70;
+    const double wps = t.p.waves * wpc / 4.0; // waves per SIMD
+    double clk_entry = (4.0 * t.p.t + 1.7) * 4.0 * wps / eff;
+    if (wps < 4) clk_entry *= 1.0 + 0.12 * (4 - wps);
+    const double wg = entries * clk_entry + (double)t.nblk * 2500.0 * wpc + 12000.0 * wpc;
+    return std::ceil(wgs / (256.0 * wpc)) * wg / 2400.0;
+}
+
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
 {
     const Geometry g = geometry(d);
@@ -218,7 +238,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
     const int kinds[2] = {3, 1};
 
     double best = -1;
-    const int nts_big[] = {4, 8, 16};
+    const int nts_big[] = {4, 8, 16}; // 8 and 16 only on request
     const int nts_small[] = {1, 2};
     const int *nts = N_hint >= 4 ? nts_big : nts_small;
     const int n_nts = N_hint >= 4 ? 3 : 2;
@@ -226,6 +246,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
     for (int a = 0; a < n_nts; ++a) {
         const int nt = nts[a];
         if (req.nt && req.nt != nt) continue;
+        if (!req.nt && nt > 4) continue;
         if (nt > 1 && nt > N_hint) continue;
         const int vec = nt % 4 == 0 ? 4 : 1;
         int last_band = 0;
@@ -246,6 +267,9 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                     for (int rows_w = 1; rows_w <= 24; ++rows_w) {
                         const int kind = kinds[ki];
                         if (req.kernel && req.kernel != kind) continue;
+                        // left to itself the library uses flat streams for tiles of 4 images and per-row
+                        // streams only for the small-batch tiles the flat kernel does not cover
+                        if (!req.kernel && (kind == 3) != (nt == 4)) continue;
                         if (kind == 3 ? (nt != 4 || !lds2_kernel_available(T, rows_w)) : !lds_kernel_available(vec, T, rows_w))
                             continue;
                         if (req.rows_w && req.rows_w != rows_w) continue;
@@ -263,7 +287,8 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                             sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band};
                             LdsTiling t;
                             if (fill_tiling(d, p, t) != SCONV_OK) continue;
-                            const double c = tiling_cost(d, t, N_hint, avg_row_nnz);
+                            const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
+                                                       : tiling_cost(d, t, N_hint, avg_row_nnz);
                             if (best < 0 || c < best) {
                                 best = c;
                                 out = t;

@@ -109,6 +109,7 @@ int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out);
 int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedFlat &out);
 int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out);
 bool lds2_kernel_available(int t, int rows_w);
+int lds2_depth(int t, int rows_w); // read-ahead depth of a flat-stream shape, 0 if there is none
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
 int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
 

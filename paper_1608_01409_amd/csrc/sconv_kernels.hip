@@ -448,6 +448,14 @@ bool lds2_kernel_available(int t, int rows_w)
     return false;
 }
 
+int lds2_depth(int t, int rows_w)
+{
+#define X(TT, RW) if (t == TT && rows_w == RW) return Lds2Asm<TT, RW>::kDepth;
+    SCONV_LDS2_SHAPES(X)
+#undef X
+    return 0;
+}
+
 int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
                 int N, void *stream, int *hip_err)
 {

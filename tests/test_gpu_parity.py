@@ -28,7 +28,9 @@ def check(layer, w, x, oracle, plan=None, images=None, what=""):
     h = B.sconv_create_csr(layer, w, plan)
     info = B.sconv_csr_info(h)
     xd = torch.from_numpy(x).cuda()
-    out = B.sconv_forward(h, xd)
+    # NaN first: an output the kernel fails to write must not pass on what an earlier case left there
+    out = torch.full((x.shape[0], layer.K, info["OH"], info["OW"]), float("nan"), device="cuda")
+    B.sconv_forward(h, xd, out)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     idx = np.arange(x.shape[0]) if images is None else np.asarray(images)
