@@ -36,14 +36,15 @@ SHAPES = [
 ]
 CH = 8                      # entries per chunk
 W = 2 * CH                  # dwords per chunk
-# SGPRs owned by the asm: s28-s31, s34-s95 (s32/s33 and everything from s96 up are left to the compiler)
+# SGPRs owned by the asm: s28-s31, s34-s99 (s32, s33, s100 and up are left to the compiler)
 SCB, SREM, SSOFF = 28, 29, 30
 SEXEC = 34
 SA, SB, SN = 36, 52, 68
 SPTR, SCNT, STMP = 84, 86, 87
 SBLK, SNBLK, SSEG = 88, 89, 90
 SBUF, SSTRIDE, SPLANE, SHW4 = 92, 93, 94, 95
-SD, SS, SNCH, STGT = SA, SA + 1, SA + 2, SA + 3   # staging temporaries: the chunk buffers are idle then
+SD, SS, SNCH, STGT = 96, 97, 98, 99              # staging temporaries
+SNXT = 31                                        # chunks in the next block's segment
 SX0, SX1 = SSEG, SSEG + 1                        # store address pair: the segment pointer is done by then
 MAX_VGPR = 128
 
@@ -99,15 +100,15 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
             emit("s_mov_b64 exec, vcc")
             emit(f"s_mov_b32 s{SD}, s{STMP}")
             emit(f"s_mov_b32 s{SS}, s{SSOFF}")
-            emit(f"s_mov_b32 s{SCNT}, s{SNCH}")
+            emit(f"s_mov_b32 vcc_lo, s{SNCH}")       # vcc is free again: channel counter
             lp = label("stj")
             emit(f"{lp}:")
             emit(f"s_mov_b32 m0, s{SD}")
             emit(f"s_add_u32 s{SD}, s{SD}, s{SPLANE}")
             emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
             emit(f"s_add_u32 s{SS}, s{SS}, s{SHW4}")
-            emit(f"s_sub_u32 s{SCNT}, s{SCNT}, 1")
-            emit(f"s_cmp_lg_u32 s{SCNT}, 0")
+            emit("s_sub_u32 vcc_lo, vcc_lo, 1")
+            emit("s_cmp_lg_u32 vcc_lo, 0")
             emit(f"s_cbranch_scc1 {lp}")
             emit(f"s_add_u32 s{STMP}, s{STMP}, {OP['slabstep']}")
         emit(f"{end}:")
@@ -163,52 +164,72 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
     emit(f"s_mov_b32 s{SBLK}, 0")
     emit(f"s_mov_b64 s[{SSEG}:{SSEG + 1}], {OP['segp']}")
     emit(f"s_mov_b32 s{SBUF}, 0")
-    emit(f"s_mov_b32 s{STGT}, {OP['ldsbase']}")
-    stage(STGT)
-
-    # ------------------------------------------------------------------ channel blocks
-    blk, nostage, segdone = label("blk"), label("nostage"), label("segdone")
-    emit(f"{blk}:")
-    emit(f"s_load_dwordx2 s[{SN}:{SN + 1}], s[{SSEG}:{SSEG + 1}], 0x0")
+    emit(f"s_load_dwordx2 s[{SN}:{SN + 1}], s[{SSEG}:{SSEG + 1}], 0x0")          # segment of block 0
     emit(f"s_load_dwordx2 s[{SN + 2}:{SN + 3}], {OP['kern']}, {hex(OFF_PAIRS)}")
     emit(f"s_add_u32 s{SSEG}, s{SSEG}, 8")
     emit(f"s_addc_u32 s{SSEG + 1}, s{SSEG + 1}, 0")
-    emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
-    emit("s_barrier")
-    emit(f"s_add_u32 s{STMP}, s{SBLK}, 1")
-    emit(f"s_cmp_ge_u32 s{STMP}, s{SNBLK}")
-    emit(f"s_cbranch_scc1 {nostage}")
-    emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
-    emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
-    stage(STGT)   # touches none of N's registers, where this block's descriptor sits
-    emit(f"{nostage}:")
-    emit(f"s_cmp_eq_u32 s{SN + 1}, 0")
-    emit(f"s_cbranch_scc1 {segdone}")
+    emit(f"s_mov_b32 s{STGT}, {OP['ldsbase']}")
+    stage(STGT)
+    # The segments of one wave slot follow each other in memory, block after block, so the two chunks the
+    # loop has read ahead when a segment ends are the first two of the next one: only block 0 loads them here.
+    emit("s_waitcnt lgkmcnt(0)")
     emit(f"s_add_u32 s{SPTR}, s{SN + 2}, s{SN}")
     emit(f"s_addc_u32 s{SPTR + 1}, s{SN + 3}, 0")
-    emit(f"s_mov_b32 s{SCNT}, s{SN + 1}")
-    emit(f"s_add_u32 s{STMP}, s{SBUF}, {OP['ldsbase']}")
-    emit(f"v_add_u32 v{VLB}, s{STMP}, {OP['lane_byte']}")
-    # stream prologue
+    emit(f"s_mov_b32 s{SNXT}, s{SN + 1}")
     emit(f"s_load_dwordx16 s[{SA}:{SA + W - 1}], s[{SPTR}:{SPTR + 1}], 0x0")
     emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], {hex(4 * W)}")
     emit(f"s_add_u32 s{SPTR}, s{SPTR}, {hex(8 * W)}")
     emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
-    emit("s_waitcnt lgkmcnt(0)")
+
+    # ------------------------------------------------------------------ channel blocks
+    blk, nostage, segdone, noreads = label("blk"), label("nostage"), label("segdone"), label("noreads")
+    emit(f"{blk}:")
+    emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
+    emit("s_barrier")
+    emit(f"s_mov_b32 s{SCNT}, s{SNXT}")
+    emit(f"s_load_dword s{SNXT}, s[{SSEG}:{SSEG + 1}], 0x4")   # chunks of the next block (one spare entry ends the table)
+    emit(f"s_add_u32 s{SSEG}, s{SSEG}, 8")
+    emit(f"s_addc_u32 s{SSEG + 1}, s{SSEG + 1}, 0")
+    # first reads of this block's stream go out before the loads of the next block are issued
+    emit(f"s_cmp_eq_u32 s{SCNT}, 0")
+    emit(f"s_cbranch_scc1 {noreads}")
+    emit(f"s_add_u32 s{STMP}, s{SBUF}, {OP['ldsbase']}")
+    emit(f"v_add_u32 v{VLB}, s{STMP}, {OP['lane_byte']}")
     for d in range(D):
         emit(f"s_lshr_b32 s{STMP}, {w1(SA, d)}, 8")
         emit(f"v_add_u32 v{VA0 + d}, s{STMP}, v{VLB}")
         for t in range(T):
             emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * 1024}")
-    loop, done = label("chunk"), label("chunkend")
+    emit(f"{noreads}:")
+    emit(f"s_add_u32 s{STMP}, s{SBLK}, 1")
+    emit(f"s_cmp_ge_u32 s{STMP}, s{SNBLK}")
+    emit(f"s_cbranch_scc1 {nostage}")
+    emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
+    emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
+    stage(STGT)
+    emit(f"{nostage}:")
+    emit(f"s_cmp_eq_u32 s{SCNT}, 0")
+    emit(f"s_cbranch_scc1 {segdone}")
+    loop, exit1, exit2 = label("chunk"), label("exita"), label("exitb")
     emit(f"{loop}:")
     body(SA, SB, SN)
-    emit(f"s_cbranch_scc0 {done}")
+    emit(f"s_cbranch_scc0 {exit1}")
     body(SB, SN, SA)
-    emit(f"s_cbranch_scc0 {done}")
+    emit(f"s_cbranch_scc0 {exit2}")
     body(SN, SA, SB)
     emit(f"s_cbranch_scc1 {loop}")
-    emit(f"{done}:")
+    emit(f"s_branch {segdone}")                 # the chunks read ahead sit in A and B already
+    emit(f"{exit1}:")                           # ... in B and N
+    for w in range(0, W, 2):
+        emit(f"s_mov_b64 s[{SA + w}:{SA + w + 1}], s[{SB + w}:{SB + w + 1}]")
+    for w in range(0, W, 2):
+        emit(f"s_mov_b64 s[{SB + w}:{SB + w + 1}], s[{SN + w}:{SN + w + 1}]")
+    emit(f"s_branch {segdone}")
+    emit(f"{exit2}:")                           # ... in N and A
+    for w in range(0, W, 2):
+        emit(f"s_mov_b64 s[{SB + w}:{SB + w + 1}], s[{SA + w}:{SA + w + 1}]")
+    for w in range(0, W, 2):
+        emit(f"s_mov_b64 s[{SA + w}:{SA + w + 1}], s[{SN + w}:{SN + w + 1}]")
     emit(f"{segdone}:")
     emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
     emit(f"s_add_u32 s{SBLK}, s{SBLK}, 1")
@@ -258,7 +279,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
         ins_ = ins_.replace(f"{OP['outp']}_LO", OP['outp']).replace(f"{OP['outp']}_HI", f"%{len(OPS)}")
         text.append(f'            "{ins_}\\n\\t"')
     clob = [f'"v{r}"' for r in range(ACC0, MAX_VGPR)]
-    clob += [f'"s{r}"' for r in list(range(28, 32)) + list(range(34, 96))]
+    clob += [f'"s{r}"' for r in list(range(28, 32)) + list(range(34, 100))]
     clob += ['"vcc"', '"scc"', '"memory"']
     return f"""
 template <>

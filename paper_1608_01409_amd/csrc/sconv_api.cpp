@@ -20,10 +20,44 @@ struct sconv_csr {
     DeviceLds dev_lds;
     DeviceDirect dev_direct;
     bool lds_uploaded = false, direct_uploaded = false;
+    int planned_n = 0;       // batch size the current LDS tiling was chosen for
     int hip_err = 0;
 };
 
 static const LdsTiling &f_tiling(const sconv_csr *h) { return h->lds_flat.t; }
+
+static bool same_plan(const sconv_plan &a, const sconv_plan &b)
+{
+    return a.kernel == b.kernel && a.nt == b.nt && a.cb == b.cb && a.waves == b.waves && a.cg == b.cg &&
+           a.rows_w == b.rows_w && a.t == b.t && a.band == b.band;
+}
+
+// Choose (or re-choose) the LDS tiling for batch size n and pack for it.  The best tiling depends on the
+// batch: with few image tiles smaller workgroups are needed to occupy every CU.
+static int plan_lds(sconv_csr *h, int n)
+{
+    const sconv_desc &d = h->desc;
+    const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
+    LdsTiling t;
+    int rc = make_lds_tiling(d, h->requested, n, avg, t);
+    if (rc) return rc;
+    h->planned_n = n;
+    if (h->has_lds && same_plan(t.p, h->flat ? h->lds_flat.t.p : h->lds.t.p)) return SCONV_OK;
+    if (h->lds_uploaded) { // hipFree waits for launches that still read the old arrays
+        release(h->dev_lds.pairs);
+        release(h->dev_lds.seg_ptr);
+        release(h->dev_lds.row_of);
+        release(h->dev_lds.store_tbl);
+        h->dev_lds = DeviceLds();
+        h->lds_uploaded = false;
+    }
+    h->has_lds = false;
+    h->flat = t.p.kernel == 3;
+    rc = h->flat ? pack_flat(d, h->canon, t, h->lds_flat) : pack_lds(d, h->canon, t, h->lds);
+    if (rc) return rc;
+    h->has_lds = true;
+    return SCONV_OK;
+}
 
 static int finish_create(sconv_csr *h, const sconv_plan *plan)
 {
@@ -31,21 +65,12 @@ static int finish_create(sconv_csr *h, const sconv_plan *plan)
     if (plan) h->requested = *plan;
     if (h->requested.kernel < 0 || h->requested.kernel > 3) return SCONV_ERR_PLAN;
     const sconv_desc &d = h->desc;
-    const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
     int rc = pack_direct(d, h->canon, h->direct);
     if (rc) return rc;
     if (h->requested.kernel != 2 && d.stride == 1) {
-        LdsTiling t;
-        // the automatic choice is tuned for large batches; small ones go to the direct kernel
-        rc = make_lds_tiling(d, h->requested, h->requested.nt ? h->requested.nt : 256, avg, t);
-        if (rc == SCONV_OK) {
-            h->flat = t.p.kernel == 3;
-            rc = h->flat ? pack_flat(d, h->canon, t, h->lds_flat) : pack_lds(d, h->canon, t, h->lds);
-            if (rc) return rc;
-            h->has_lds = true;
-        } else if (h->requested.kernel != 0) {
-            return rc;
-        }
+        // tuned for a large batch until the first forward call says otherwise; small ones go to the direct kernel
+        rc = plan_lds(h, h->requested.nt ? h->requested.nt : 256);
+        if (rc != SCONV_OK && h->requested.kernel != 0) return rc;
     } else if (h->requested.kernel == 1 || h->requested.kernel == 3) {
         return SCONV_ERR_PLAN;
     }
@@ -166,6 +191,17 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
     if (!h || !in || !out) return SCONV_ERR_NULL;
     if (N < 1) return SCONV_ERR_BATCH;
     bool use_lds = h->has_lds;
+    // a tiling the library chose itself follows the batch size (only when none of its fields was requested)
+    const sconv_plan &rq = h->requested;
+    const bool free_choice = !rq.nt && !rq.cb && !rq.waves && !rq.cg && !rq.rows_w && !rq.t && !rq.band;
+    if (use_lds && free_choice && N >= 4 && N != h->planned_n) {
+        try {
+            const int prc = plan_lds(h, N);
+            if (prc) return prc;
+        } catch (const std::bad_alloc &) {
+            return SCONV_ERR_NOMEM;
+        }
+    }
     const LdsTiling &til = h->flat ? h->lds_flat.t : h->lds.t;
     if (use_lds && h->requested.kernel == 0 && N < 4 && til.p.nt >= 4) use_lds = false;
     int rc;

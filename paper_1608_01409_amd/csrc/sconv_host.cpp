@@ -220,13 +220,15 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     const int wpc = std::max(1, std::min(by_lds, 16 / t.p.waves));
     const double rows_wave = (double)g.Kg / (t.nkt * t.rg);
     const double entries = rows_wave * avg_row_nnz + 3.5 * t.nblk;
-    const int depth = lds2_depth(t.p.t, t.p.rows_w);
-    const double eff = depth * t.p.t >= 6 ? 0.78 : 0.70;
-    const double wps = t.p.waves * wpc / 4.0; // waves per SIMD
-    double clk_entry = (4.0 * t.p.t + 1.7) * 4.0 * wps / eff;
-    if (wps < 4) clk_entry *= 1.0 + 0.12 * (4 - wps);
-    const double wg = entries * clk_entry + (double)t.nblk * 2500.0 * wpc + 12000.0 * wpc;
-    return std::ceil(wgs / (256.0 * wpc)) * wg / 2400.0;
+    const double cu_wgs = std::ceil(wgs / 256.0);             // workgroups one CU has to run ...
+    const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
+    const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
+    double eff = wps >= 4 ? 0.78 : wps >= 3 ? 0.72 : wps >= 2 ? 0.68 : 0.42;
+    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.92; // shallow read-ahead ring
+    const double simd_clk = t.p.waves * entries * (4.0 * t.p.t + 1.7); // VALU clocks per SIMD, one workgroup
+    double group = m * simd_clk / eff + t.nblk * 1500.0 + 14000.0;
+    if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
+    return std::ceil(cu_wgs / m) * group / 2400.0;
 }
 
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
@@ -365,24 +367,58 @@ int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packed
     return SCONV_OK;
 }
 
-// Rows of one group dealt to the group's wave slots, longest first, boustrophedon (see pack_lds).
+// Rows of one group dealt to the group's wave slots for the flat-stream kernel.  Every wave of a workgroup
+// meets the others at a barrier after each channel block, so what has to be even is the number of nonzeros a
+// slot holds in EACH block, not only its total.  Greedy: rows in descending order of their nonzero count,
+// each to the slot (with a free row) whose fullest block stays smallest, ties to the smaller total.  Rows
+// without nonzeros are dealt like any other and fill what is left.
 static int deal_rows(const sconv_desc &d, const Canonical &c, const LdsTiling &t, std::vector<int32_t> &row_of)
 {
     const Geometry g = geometry(d);
-    const int rows_w = t.p.rows_w;
-    const int waves_per_group = t.nkt * t.rg;
+    const int rows_w = t.p.rows_w, nblk = t.nblk, cb = t.p.cb;
+    const int slots = t.nkt * t.rg;
     row_of.assign((size_t)t.wave_slots * rows_w, -1);
+    std::vector<int> per_blk((size_t)g.Kg * nblk);
+    std::vector<int64_t> load((size_t)slots * nblk), total(slots);
+    std::vector<int> used(slots);
     for (int grp = 0; grp < d.groups; ++grp) {
-        std::vector<int> rows(g.Kg);
-        std::iota(rows.begin(), rows.end(), grp * g.Kg);
-        std::stable_sort(rows.begin(), rows.end(), [&](int a, int b) {
-            return c.rowptr[a + 1] - c.rowptr[a] > c.rowptr[b + 1] - c.rowptr[b];
-        });
+        std::fill(per_blk.begin(), per_blk.end(), 0);
         for (int i = 0; i < g.Kg; ++i) {
-            const int round = i / waves_per_group, posn = i % waves_per_group;
-            const int w = (round & 1) ? waves_per_group - 1 - posn : posn;
-            if (round >= rows_w) return SCONV_ERR_PLAN;
-            row_of[((size_t)grp * waves_per_group + w) * rows_w + round] = rows[i];
+            const int k = grp * g.Kg + i;
+            for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
+                const int ca = c.off[j] / (g.Wp * g.Hp);
+                per_blk[(size_t)i * nblk + (ca - grp * g.Cg) / cb]++;
+            }
+        }
+        std::vector<int> rows(g.Kg);
+        std::iota(rows.begin(), rows.end(), 0);
+        std::stable_sort(rows.begin(), rows.end(), [&](int a, int b) {
+            const int ka = grp * g.Kg + a, kb = grp * g.Kg + b;
+            return c.rowptr[ka + 1] - c.rowptr[ka] > c.rowptr[kb + 1] - c.rowptr[kb];
+        });
+        std::fill(load.begin(), load.end(), 0);
+        std::fill(total.begin(), total.end(), 0);
+        std::fill(used.begin(), used.end(), 0);
+        for (int i : rows) {
+            const int *r = &per_blk[(size_t)i * nblk];
+            int best = -1;
+            int64_t best_max = 0, best_tot = 0;
+            for (int s2 = 0; s2 < slots; ++s2) {
+                if (used[s2] >= rows_w) continue;
+                int64_t mx = 0;
+                for (int b = 0; b < nblk; ++b) mx = std::max(mx, load[(size_t)s2 * nblk + b] + r[b]);
+                if (best < 0 || mx < best_max || (mx == best_max && total[s2] < best_tot)) {
+                    best = s2;
+                    best_max = mx;
+                    best_tot = total[s2];
+                }
+            }
+            if (best < 0) return SCONV_ERR_PLAN; // cannot happen: slots * rows_w >= Kg
+            for (int b = 0; b < nblk; ++b) {
+                load[(size_t)best * nblk + b] += r[b];
+                total[best] += r[b];
+            }
+            row_of[((size_t)grp * slots + best) * rows_w + used[best]++] = grp * g.Kg + i;
         }
     }
     return SCONV_OK;
@@ -396,7 +432,7 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
     out.t = t;
     int rc = deal_rows(d, c, t, out.row_of);
     if (rc) return rc;
-    out.seg.assign((size_t)t.wave_slots * t.nblk * 2, 0);
+    out.seg.assign((size_t)t.wave_slots * t.nblk * 2 + 2, 0); // one spare entry: the kernel looks one block ahead
     out.pairs.clear();
     out.pairs.reserve(c.val.size() + (size_t)t.wave_slots * t.nblk * 4);
     const uint64_t pad_entry = (uint64_t)(t.zero_page << 8) << 32;

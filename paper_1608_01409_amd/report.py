@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Measurement reports beyond the one-line benchmark: the density sweep with the
+roofline model's prediction and the dense-convolution crossover (Section 2.2,
+Section 3.2 / Figure 5 of the paper), the skewed guided-pruning-like patterns,
+and the GoogLeNet-like and strided layers.
+
+    python -m paper_1608_01409_amd.report sweep|skewed|extra|all [--iters K]
+
+Every input is seeded and synthetic (paper_1608_01409_amd/workloads.py).  The
+dense reference is the vendor's fp32 convolution reached through
+torch.nn.functional.conv2d (the paper uses the vendor SGEMM as its proxy for
+dense convolution, Section 3.2).  Prints a text table and one JSON line per
+table row.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import sys
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as wl
+
+
+def time_gpu(fn, iters: int, warm: int = 3) -> float:
+    """Mean milliseconds per call, HIP events on the current stream, back-to-back launches."""
+    for _ in range(warm):
+        fn()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def time_sparse(layer, w, xd, iters, plan=None):
+    h = B.sconv_create_csr(layer, w, plan)
+    info = B.sconv_csr_info(h)
+    out = torch.empty((xd.shape[0], layer.K, info["OH"], info["OW"]), dtype=torch.float32, device="cuda")
+    ms = time_gpu(lambda: B.sconv_forward(h, xd, out), iters)
+    return ms, info, h
+
+
+def time_dense(layer, xd, iters):
+    """Vendor fp32 dense convolution of the same shape (all weights nonzero)."""
+    torch.backends.cudnn.allow_tf32 = False
+    torch.backends.cuda.matmul.allow_tf32 = False
+    wd = torch.randn((layer.K, layer.Cg, layer.R, layer.S), device="cuda") * 0.01
+    fn = lambda: torch.nn.functional.conv2d(xd, wd, None, layer.stride, layer.pad, 1, layer.groups)
+    return time_gpu(fn, iters, warm=5)
+
+
+def crossover(xs, t_sparse, t_dense):
+    """Density at which the sparse time reaches the dense time: log-linear interpolation between the two
+    sweep points that bracket it; None if sparse stays faster (or slower) over the whole sweep."""
+    for i in range(len(xs) - 1):
+        a, b = t_sparse[i] - t_dense, t_sparse[i + 1] - t_dense
+        if a <= 0 < b:
+            la, lb = math.log(xs[i]), math.log(xs[i + 1])
+            ta, tb = math.log(t_sparse[i]), math.log(t_sparse[i + 1])
+            f = (math.log(t_dense) - ta) / (tb - ta)
+            return math.exp(la + f * (lb - la))
+    return None
+
+
+def emit(row):
+    print(json.dumps(row), flush=True)
+
+
+def report_sweep(iters):
+    print("# density sweep, AlexNet conv2-5, batch 256 (configuration 3)")
+    print(f"{'layer':6s} {'x':>5s} {'nnz':>8s} {'t_meas us':>10s} {'t_model us':>10s} {'TFLOP/s':>8s} "
+          f"{'t_dense us':>10s} {'speedup':>8s} {'model spd':>9s}")
+    for li, (name, N, _) in enumerate(wl.CONFIGS[1]):
+        layer = wl.LAYERS[name]
+        xs, ts = [], []
+        x0, _ = wl.make_case(2, li, layer, N, 0.1)
+        xd = torch.from_numpy(x0).cuda()
+        t_dense = time_dense(layer, xd, iters) * 1e-3
+        pred1 = None
+        for dens in wl.SWEEP_DENSITIES:
+            _, w = wl.make_case(2, li, layer, 1, dens)
+            ms, info, h = time_sparse(layer, w, xd, iters)
+            pred = B.sconv_model_predict(layer, N, dens, h)
+            pred1 = pred
+            flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
+            xs.append(pred["density"])
+            ts.append(ms * 1e-3)
+            row = dict(report="sweep", layer=name, density=dens, realised=pred["density"], nnz=info["nnz"],
+                       t_meas_us=ms * 1e3, t_model_us=pred["t_sparse"] * 1e6, tflops=flops / ms / 1e9,
+                       t_dense_us=t_dense * 1e6, speedup=t_dense / (ms * 1e-3), model_speedup=pred["speedup"],
+                       bandwidth_bound=bool(pred["bandwidth_bound"]), plan=info["plan"])
+            print(f"{name:6s} {dens:5.2f} {info['nnz']:8d} {ms*1e3:10.1f} {pred['t_sparse']*1e6:10.1f} "
+                  f"{flops/ms/1e9:8.2f} {t_dense*1e6:10.1f} {t_dense/(ms*1e-3):8.2f} {pred['speedup']:9.2f}")
+            emit(row)
+        xc = crossover(xs, ts, t_dense)
+        # model's crossover with the measured dense rate in place of the default
+        m = B.sconv_machine_gfx950()
+        flops_dense = pred1["flops_dense"]
+        m.dense_flops = flops_dense / t_dense
+        pm = B.sconv_model_predict(layer, N, 0.1, None, m)
+        ratio = (xc / pm["x_lower"]) if xc else None
+        print(f"{name}: measured crossover x = {xc}, model x_lower = {pm['x_lower']:.3f} (alpha {pm['alpha']:.2f}, "
+              f"dense {m.dense_flops/1e12:.1f} TFLOP/s measured), model x_upper = {pm['x_upper']:.4f}, ratio {ratio}")
+        emit(dict(report="crossover", layer=name, measured=xc, model_x_lower=pm["x_lower"], model_x_upper=pm["x_upper"],
+                  alpha=pm["alpha"], dense_tflops=m.dense_flops / 1e12, ratio=ratio))
+
+
+def report_skewed(iters):
+    print("# skewed per-row densities, 20% empty rows, clustered columns, batch 256 (configuration 4)")
+    for li, name in enumerate(("conv3", "conv4")):
+        layer = wl.LAYERS[name]
+        x, w = wl.make_case(3, li, layer, 256, 0.10, skewed=True)
+        xd = torch.from_numpy(x).cuda()
+        nnz_row = (w.reshape(layer.K, -1) != 0).sum(1)
+        ms, info, _ = time_sparse(layer, w, xd, iters)
+        flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * 256
+        # the same number of nonzeros spread uniformly, for comparison
+        dens = info["nnz"] / w.size
+        _, wu = wl.make_case(3, li + 2, layer, 1, dens)
+        msu, infou, _ = time_sparse(layer, wu, xd, iters)
+        flu = 2.0 * infou["nnz"] * infou["OH"] * infou["OW"] * 256
+        row = dict(report="skewed", layer=name, nnz=info["nnz"], empty_rows=int((nnz_row == 0).sum()),
+                   max_row=int(nnz_row.max()), mean_row=float(nnz_row.mean()), t_us=ms * 1e3, tflops=flops / ms / 1e9,
+                   uniform_t_us=msu * 1e3, uniform_tflops=flu / msu / 1e9, plan=info["plan"])
+        print(f"{name}: nnz {info['nnz']} rows empty {row['empty_rows']} max/mean {row['max_row']}/{row['mean_row']:.0f}: "
+              f"{ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s; uniform mask of the same density: {msu*1e3:.1f} us "
+              f"{row['uniform_tflops']:.2f} TFLOP/s")
+        emit(row)
+
+
+def report_extra(iters):
+    print("# GoogLeNet-inception-like and strided layers, batch 64 (configuration 5)")
+    for li, (name, N, dens) in enumerate(wl.CONFIGS[4]):
+        layer = wl.LAYERS[name]
+        x, w = wl.make_case(4, li, layer, N, dens)
+        xd = torch.from_numpy(x).cuda()
+        ms, info, h = time_sparse(layer, w, xd, iters)
+        t_dense = time_dense(layer, xd, iters)
+        flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
+        pred = B.sconv_model_predict(layer, N, dens, h)
+        row = dict(report="extra", layer=name, N=N, density=dens, nnz=info["nnz"], t_us=ms * 1e3, tflops=flops / ms / 1e9,
+                   t_dense_us=t_dense * 1e3, speedup=t_dense / ms, t_model_us=pred["t_sparse"] * 1e6, plan=info["plan"])
+        print(f"{name}: N {N} x {dens} nnz {info['nnz']}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s, dense {t_dense*1e3:.1f} us, "
+              f"speedup {t_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us, plan {info['plan']}")
+        emit(row)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("what", choices=["sweep", "skewed", "extra", "all"])
+    ap.add_argument("--iters", type=int, default=20)
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("report: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.what in ("sweep", "all"):
+        report_sweep(args.iters)
+    if args.what in ("skewed", "all"):
+        report_skewed(args.iters)
+    if args.what in ("extra", "all"):
+        report_extra(args.iters)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
