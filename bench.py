@@ -30,6 +30,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mb", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (a known-size reference for "
+                         "scaling the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (batch-sharded data parallelism needs no "
@@ -72,6 +75,13 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_probe_mb:
+        src = torch.empty(args.copy_probe_mb * 2 ** 20 // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+    for L in layers:  # the tiling follows the batch size at the first call
+        L["plan"] = B.sconv_csr_info(L["h"])["plan"]
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
           for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -97,12 +107,13 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(layers[dom]["name"])
+            traffic = json.load(open(tpath)).get(layers[dom]["name"], {}).get("bytes")
         except (OSError, ValueError):
             traffic = None
     roofline = dict(bound="alu", achieved=achieved, peak=PEAK_FMA_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_FMA_TFLOPS, 4), traffic=traffic,
-                    kernel=f"sconv_lds_kernel on {layers[dom]['name']}",
+                    kernel=("sconv_lds2_kernel" if layers[dom]["plan"]["kernel"] == 3 else "sconv_lds_kernel") +
+                    f" on {layers[dom]['name']}",
                     frac_of_published_fp32_vector=round(achieved / PEAK_FP32_PUBLISHED_TFLOPS, 4),
                     step_frac=round(value / 1e3 / PEAK_FMA_TFLOPS, 4), per_layer=per_layer)
 

@@ -1,0 +1,97 @@
+#!/usr/bin/env python3
+"""Turn raw rocprofv3 output of bench.py runs into the short text summaries kept
+under profiles/ and into profiles/hbm_traffic.json (HBM bytes per launch of each
+layer's kernel, which bench.py reports as roofline.traffic).
+
+    python -m paper_1608_01409_amd.profile_summary RAW_DIR OUT_DIR
+
+RAW_DIR holds one sub-directory per profiler run, named as in profiles/README.md:
+kt (kernel trace + stats), fetch (FETCH_SIZE), write (WRITE_SIZE), sq1, sq2
+(SQ counters).  The byte counters are scaled by what the same counter reads for
+the plain device copy bench.py launches with --copy-probe-mb (a kernel that
+moves a known number of bytes each way).
+"""
+from __future__ import annotations
+
+import csv
+import glob
+import json
+import os
+import sys
+from collections import defaultdict
+
+LAYERS = ["conv2", "conv3", "conv4", "conv5"]
+COPY_MB = 256
+
+
+def find(raw, run, suffix):
+    hits = glob.glob(os.path.join(raw, run, "**", f"*{suffix}"), recursive=True)
+    return hits[0] if hits else None
+
+
+def counters(raw, run):
+    """{counter: {"layers": {layer: mean per launch}, "copy": value}} for one --pmc run."""
+    path = find(raw, run, "counter_collection.csv")
+    if not path:
+        return {}
+    rows = list(csv.DictReader(open(path)))
+    per = defaultdict(lambda: defaultdict(list))   # counter -> dispatch -> values
+    name = {}
+    for r in rows:
+        d = int(r["Dispatch_Id"])
+        per[r["Counter_Name"]][d].append(float(r["Counter_Value"]))
+        name[d] = r["Kernel_Name"]
+    sconv = sorted(d for d, n in name.items() if "sconv_lds" in n or "sconv_direct" in n)
+    copies = sorted(d for d, n in name.items() if "copy" in n.lower() or "elementwise" in n.lower())
+    out = {}
+    for c, by_d in per.items():
+        lay = defaultdict(list)
+        for i, d in enumerate(sconv):
+            lay[LAYERS[i % len(LAYERS)]].append(sum(by_d.get(d, [0.0])))
+        # the probe copy is the largest copy-like dispatch
+        cp = max((sum(by_d.get(d, [0.0])) for d in copies), default=None)
+        out[c] = {"layers": {k: sum(v) / len(v) for k, v in lay.items()}, "copy": cp, "launches": len(sconv)}
+    return out
+
+
+def main() -> int:
+    raw, out_dir = sys.argv[1], sys.argv[2]
+    os.makedirs(out_dir, exist_ok=True)
+    lines = []
+    kt = find(raw, "kt", "kernel_stats.csv")
+    if kt:
+        lines.append("kernel trace (rocprofv3 --kernel-trace --stats), all launches of bench.py's run")
+        lines.append(f"{'kernel':70s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}")
+        for r in csv.DictReader(open(kt)):
+            lines.append(f"{r['Name'][:70]:70s} {r['Calls']:>6s} {float(r['AverageNs'])/1e3:9.2f} "
+                         f"{float(r['MinNs'])/1e3:9.2f} {float(r['MaxNs'])/1e3:9.2f} {float(r['Percentage']):6.2f}")
+        lines.append("")
+    traffic = {}
+    fetch, write = counters(raw, "fetch").get("FETCH_SIZE"), counters(raw, "write").get("WRITE_SIZE")
+    if fetch and write and fetch["copy"] and write["copy"]:
+        expect_kib = COPY_MB * 1024.0
+        fs, ws = expect_kib / fetch["copy"], expect_kib / write["copy"]
+        lines.append(f"HBM traffic per launch (FETCH_SIZE / WRITE_SIZE, KiB; scale factors from a {COPY_MB} MiB copy: "
+                     f"read x{fs:.3f}, write x{ws:.3f})")
+        for l in LAYERS:
+            rd = fetch["layers"].get(l, 0.0) * fs * 1024.0
+            wr = write["layers"].get(l, 0.0) * ws * 1024.0
+            traffic[l] = {"read_bytes": round(rd), "write_bytes": round(wr), "bytes": round(rd + wr)}
+            lines.append(f"  {l}: read {rd/1e6:8.1f} MB  write {wr/1e6:8.1f} MB")
+        lines.append("")
+        json.dump(traffic, open(os.path.join(out_dir, "hbm_traffic.json"), "w"), indent=1)
+    for run in ("sq1", "sq2"):
+        cs = counters(raw, run)
+        if cs:
+            lines.append(f"SQ counters per launch ({run})")
+            for c in sorted(cs):
+                lines.append(f"  {c:28s} " + "  ".join(f"{l} {cs[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
+            lines.append("")
+    text = "\n".join(lines)
+    print(text)
+    open(os.path.join(out_dir, "_summary_body.txt"), "w").write(text)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
