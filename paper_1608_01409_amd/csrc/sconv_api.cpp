@@ -21,6 +21,13 @@ struct sconv_csr {
     DeviceDirect dev_direct;
     bool lds_uploaded = false, direct_uploaded = false;
     int planned_n = 0;       // batch size the current LDS tiling was chosen for
+    // the layer the LDS kernels run: the layer itself, or for stride > 1 its stride-1 form over phase images
+    bool phased = false;
+    sconv_desc kdesc;
+    Canonical kcanon;        // filled only when phased
+    void *phase_buf = nullptr;
+    size_t phase_bytes = 0;
+    const Canonical &kc() const { return phased ? kcanon : canon; }
     int hip_err = 0;
 };
 
@@ -36,7 +43,7 @@ static bool same_plan(const sconv_plan &a, const sconv_plan &b)
 // batch: with few image tiles smaller workgroups are needed to occupy every CU.
 static int plan_lds(sconv_csr *h, int n)
 {
-    const sconv_desc &d = h->desc;
+    const sconv_desc &d = h->kdesc;
     const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
     LdsTiling t;
     int rc = make_lds_tiling(d, h->requested, n, avg, t);
@@ -53,7 +60,7 @@ static int plan_lds(sconv_csr *h, int n)
     }
     h->has_lds = false;
     h->flat = t.p.kernel == 3;
-    rc = h->flat ? pack_flat(d, h->canon, t, h->lds_flat) : pack_lds(d, h->canon, t, h->lds);
+    rc = h->flat ? pack_flat(d, h->kc(), t, h->lds_flat) : pack_lds(d, h->kc(), t, h->lds);
     if (rc) return rc;
     h->has_lds = true;
     return SCONV_OK;
@@ -67,7 +74,17 @@ static int finish_create(sconv_csr *h, const sconv_plan *plan)
     const sconv_desc &d = h->desc;
     int rc = pack_direct(d, h->canon, h->direct);
     if (rc) return rc;
-    if (h->requested.kernel != 2 && d.stride == 1) {
+    h->kdesc = d;
+    if (d.stride > 1 && h->requested.kernel != 2) {
+        // phase images; layers whose virtual form is out of range keep the direct kernel
+        sconv_desc v;
+        phase_desc(d, v);
+        if (validate_desc(v) == SCONV_OK && phase_canonical(d, h->canon, h->kcanon) == SCONV_OK) {
+            h->kdesc = v;
+            h->phased = true;
+        }
+    }
+    if (h->requested.kernel != 2 && (d.stride == 1 || h->phased)) {
         // tuned for a large batch until the first forward call says otherwise; small ones go to the direct kernel
         rc = plan_lds(h, h->requested.nt ? h->requested.nt : 256);
         if (rc != SCONV_OK && h->requested.kernel != 0) return rc;
@@ -173,7 +190,12 @@ extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowp
     try {
         if (which == 1) {
             if (!h->has_lds) return SCONV_ERR_PLAN;
-            rc = h->flat ? unpack_flat(h->desc, h->lds_flat, c) : unpack_lds(h->desc, h->lds, c);
+            rc = h->flat ? unpack_flat(h->kdesc, h->lds_flat, c) : unpack_lds(h->kdesc, h->lds, c);
+            if (!rc && h->phased) {
+                Canonical real;
+                rc = unphase_canonical(h->desc, c, real);
+                c = std::move(real);
+            }
         } else if (which == 2) {
             rc = unpack_direct(h->desc, h->direct, c);
         } else {
@@ -205,6 +227,21 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
     const LdsTiling &til = h->flat ? h->lds_flat.t : h->lds.t;
     if (use_lds && h->requested.kernel == 0 && N < 4 && til.p.nt >= 4) use_lds = false;
     int rc;
+    if (use_lds && h->phased) {
+        // re-order the input into phase images (scratch owned by the handle, grown on demand)
+        const size_t need = (size_t)N * h->kdesc.C * h->kdesc.H * h->kdesc.W * sizeof(float);
+        if (need > h->phase_bytes) {
+            release(h->phase_buf);
+            h->phase_buf = nullptr;
+            h->phase_bytes = 0;
+            rc = upload(nullptr, need, &h->phase_buf, &h->hip_err);
+            if (rc) return rc;
+            h->phase_bytes = need;
+        }
+        rc = launch_phase(h->desc, h->kdesc, in, static_cast<float *>(h->phase_buf), N, hip_stream, &h->hip_err);
+        if (rc) return rc;
+        in = static_cast<const float *>(h->phase_buf);
+    }
     if (use_lds && h->flat) {
         if (!h->lds_uploaded) {
             const PackedFlat &f = h->lds_flat;
@@ -215,7 +252,7 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
             if (rc) return rc;
             h->lds_uploaded = true;
         }
-        return launch_lds2(h->desc, f_tiling(h), h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+        return launch_lds2(h->kdesc, f_tiling(h), h->dev_lds, in, out, N, hip_stream, &h->hip_err);
     }
     if (use_lds) {
         if (!h->lds_uploaded) {
@@ -225,7 +262,7 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
             if (rc) return rc;
             h->lds_uploaded = true;
         }
-        return launch_lds(h->desc, h->lds.t, h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+        return launch_lds(h->kdesc, h->lds.t, h->dev_lds, in, out, N, hip_stream, &h->hip_err);
     }
     if (!h->direct_uploaded) {
         rc = upload(h->direct.rowptr.data(), h->direct.rowptr.size() * 4, &h->dev_direct.rowptr, &h->hip_err);
@@ -245,6 +282,7 @@ extern "C" void sconv_destroy_csr(sconv_csr *h)
     release(h->dev_lds.seg_ptr);
     release(h->dev_lds.row_of);
     release(h->dev_lds.store_tbl);
+    release(h->phase_buf);
     release(h->dev_direct.rowptr);
     release(h->dev_direct.trip);
     delete h;

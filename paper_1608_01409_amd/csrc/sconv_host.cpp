@@ -571,6 +571,78 @@ int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out)
     return SCONV_OK;
 }
 
+// ------------------------------------------------------------------ strided layers as phase images
+
+void phase_desc(const sconv_desc &d, sconv_desc &v)
+{
+    const Geometry g = geometry(d);
+    const int s = d.stride;
+    v = d;
+    v.C = d.C * s * s;
+    v.R = ceil_div(d.R, s);
+    v.S = ceil_div(d.S, s);
+    v.H = g.OH + v.R - 1;
+    v.W = g.OW + v.S - 1;
+    v.stride = 1;
+    v.pad = 0;
+}
+
+int phase_canonical(const sconv_desc &d, const Canonical &c, Canonical &vc)
+{
+    const Geometry g = geometry(d);
+    sconv_desc v;
+    phase_desc(d, v);
+    const Geometry gv = geometry(v);
+    const int s = d.stride;
+    std::vector<std::vector<std::pair<int32_t, float>>> rows(d.K);
+    for (int k = 0; k < d.K; ++k) {
+        const int grp = k / g.Kg;
+        for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
+            const int off = c.off[j];
+            const int t = off % g.Wp, r = (off / g.Wp) % g.Hp, ca = off / (g.Wp * g.Hp);
+            const int cl = ca - grp * g.Cg;
+            const int va = grp * gv.Cg + (cl * s + r % s) * s + t % s;
+            rows[k].push_back({(va * gv.Hp + r / s) * gv.Wp + t / s, c.val[j]});
+        }
+    }
+    sort_rows_by_offset(v, rows, vc);
+    // colidx of the virtual layer, for completeness: (v_local*R' + r')*S' + t'
+    vc.colidx.resize(vc.off.size());
+    for (int k = 0; k < d.K; ++k) {
+        const int grp = k / g.Kg;
+        for (int j = vc.rowptr[k]; j < vc.rowptr[k + 1]; ++j) {
+            const int off = vc.off[j];
+            const int t = off % gv.Wp, r = (off / gv.Wp) % gv.Hp, va = off / (gv.Wp * gv.Hp);
+            vc.colidx[j] = ((va - grp * gv.Cg) * v.R + r) * v.S + t;
+        }
+    }
+    return SCONV_OK;
+}
+
+int unphase_canonical(const sconv_desc &d, const Canonical &vc, Canonical &out)
+{
+    const Geometry g = geometry(d);
+    sconv_desc v;
+    phase_desc(d, v);
+    const Geometry gv = geometry(v);
+    const int s = d.stride;
+    std::vector<std::vector<std::pair<int32_t, float>>> rows(d.K);
+    for (int k = 0; k < d.K; ++k) {
+        const int grp = k / g.Kg;
+        for (int j = vc.rowptr[k]; j < vc.rowptr[k + 1]; ++j) {
+            const int off = vc.off[j];
+            const int t2 = off % gv.Wp, r2 = (off / gv.Wp) % gv.Hp, va = off / (gv.Wp * gv.Hp);
+            const int vl = va - grp * gv.Cg;
+            const int px = vl % s, py = (vl / s) % s, cl = vl / (s * s);
+            const int r = r2 * s + py, t = t2 * s + px;
+            if (r >= d.R || t >= d.S) return SCONV_ERR_CSR;
+            rows[k].push_back({((grp * g.Cg + cl) * g.Hp + r) * g.Wp + t, vc.val[j]});
+        }
+    }
+    sort_rows_by_offset(d, rows, out);
+    return SCONV_OK;
+}
+
 // Direct kernel: per nonzero the value, the offset of (c, r-pad, s-pad) in the UNPADDED image
 // (may be negative), and (r-pad, s-pad) for the bounds test that stands in for the zero padding.
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out)

@@ -113,6 +113,17 @@ int lds2_depth(int t, int rows_w); // read-ahead depth of a flat-stream shape, 0
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
 int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
 
+// Strided layers on the LDS kernels.  With stride s the input rows that one filter row r touches are
+// y*s + r: split r = r'*s + py and they become rows y + r' of the "phase image" py (every s-th row of the
+// padded image, starting at py), and the same along x.  A strided layer is therefore a stride-1, pad-0 layer
+// over Cg*s*s virtual channels (c, py, px) of size Hq x Wq = (OH + R' - 1) x (OW + S' - 1) with an R' x S'
+// filter, R' = ceil(R/s): no input element is duplicated, only re-ordered (Section 2.1 allows any layout
+// function f that is additive in the output position).  phase_desc gives that layer, phase_canonical its
+// CSR; unphase_canonical maps offsets of the virtual layer back to the real one.
+void phase_desc(const sconv_desc &d, sconv_desc &v);
+int phase_canonical(const sconv_desc &d, const Canonical &c, Canonical &vc);
+int unphase_canonical(const sconv_desc &d, const Canonical &vc, Canonical &out);
+
 // Device side (sconv_kernels.hip)
 struct DeviceLds {
     void *pairs = nullptr, *seg_ptr = nullptr, *row_of = nullptr, *store_tbl = nullptr;
@@ -124,6 +135,8 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
                int N, void *stream, int *hip_err);
 int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
                 int N, void *stream, int *hip_err);
+// in [N][C][H][W] -> q [N][C*s*s][Hq][Wq], zero padding written out
+int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, float *q, int N, void *stream, int *hip_err);
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
                   void *stream, int *hip_err);
 int upload(const void *host, size_t bytes, void **dev, int *hip_err);

@@ -498,6 +498,50 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     return SCONV_ERR_PLAN;
 }
 
+// Phase images of a strided layer: q[n][(c*s + py)*s + px][Y][X] = in_pad[n][c][Y*s + py][X*s + px], the
+// zero padding written out.  One thread per element of q; consecutive threads write consecutive X.
+struct PhaseArgs {
+    const float *in;
+    float *q;
+    int C, H, W, s, pad, Hq, Wq;
+    long long total;
+};
+
+__global__ void __launch_bounds__(256) sconv_phase_kernel(const PhaseArgs a)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.total) return;
+    const int X = (int)(idx % a.Wq);
+    long long rest = idx / a.Wq;
+    const int Y = (int)(rest % a.Hq);
+    rest /= a.Hq;
+    const int cv = (int)(rest % (a.C * a.s * a.s));
+    const long long n = rest / (a.C * a.s * a.s);
+    const int px = cv % a.s, py = (cv / a.s) % a.s, c = cv / (a.s * a.s);
+    const int iy = Y * a.s + py - a.pad, ix = X * a.s + px - a.pad;
+    float v = 0.f;
+    if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) v = a.in[((n * a.C + c) * a.H + iy) * a.W + ix];
+    a.q[idx] = v;
+}
+
+int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, float *q, int N, void *stream, int *hip_err)
+{
+    PhaseArgs a;
+    a.in = in;
+    a.q = q;
+    a.C = d.C; a.H = d.H; a.W = d.W; a.s = d.stride; a.pad = d.pad; a.Hq = v.H; a.Wq = v.W;
+    a.total = (long long)N * v.C * v.H * v.W;
+    const long long gx = (a.total + 255) / 256;
+    if (gx > 0x7fffffff) return SCONV_ERR_RANGE;
+    hipLaunchKernelGGL(sconv_phase_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
                   void *stream, int *hip_err)
 {

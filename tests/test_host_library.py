@@ -63,7 +63,7 @@ def test_lowering_bit_exact_and_packings_round_trip(oracle, layer, density):
     info = B.sconv_csr_info(h)
     assert info["nnz"] == len(o_val) and (info["OH"], info["OW"]) == (layer.OH, layer.OW)
     which = [2] + ([1] if info["plan"]["kernel"] in (1, 3) else [])
-    assert (info["plan"]["kernel"] in (1, 3)) == (layer.stride == 1)
+    assert info["plan"]["kernel"] in (1, 3)   # strided layers run the same kernels over their phase images
     for wh in which:
         r2, o2, v2 = B.sconv_csr_unpack(h, wh)
         assert np.array_equal(r2, o_rowptr) and np.array_equal(o2, o_off)
@@ -151,8 +151,11 @@ def test_error_paths():
         assert e.value.status == B.ERR["CSR"], (rp, ci)
     # plans that cannot run
     with pytest.raises(B.SconvError) as e:
-        B.sconv_create_csr(wl.small_layer(stride=2), w, dict(kernel=1))
+        B.sconv_create_csr(layer, w, dict(kernel=3, nt=8, cb=4, waves=8, cg=1, rows_w=6, t=3))  # flat streams: nt = 4 only
     assert e.value.status == B.ERR["PLAN"]
+    # a strided layer runs the LDS kernels over its phase images, also on request
+    hs = B.sconv_create_csr(wl.small_layer(stride=2), w, dict(kernel=1))
+    assert B.sconv_csr_info(hs)["plan"]["kernel"] == 1
     with pytest.raises(B.SconvError) as e:
         B.sconv_create_csr(layer, w, dict(kernel=1, nt=4, cb=4, waves=8, cg=1, rows_w=6, t=1))  # too few chunks
     assert e.value.status == B.ERR["PLAN"]
@@ -180,6 +183,8 @@ def test_automatic_plans_for_the_benchmark_layers():
         p = B.sconv_csr_info(h)["plan"]
         assert p["kernel"] in (1, 3) and p["nt"] % 4 == 0, (name, p)
     h = B.sconv_create_csr(wl.LAYERS["conv1"], rand_w(wl.LAYERS["conv1"], 0.3, seed=2))
+    assert B.sconv_csr_info(h)["plan"]["kernel"] == 3
+    h = B.sconv_create_csr(wl.LAYERS["conv1"], rand_w(wl.LAYERS["conv1"], 0.3, seed=2), dict(kernel=2))
     assert B.sconv_csr_info(h)["plan"]["kernel"] == 2
 
 
