@@ -141,7 +141,9 @@ typedef struct {
     double fma_flops;         /* FP32 multiply-add ceiling of the sparse kernel, FLOP/s */
     double lds_bytes_per_s;   /* LDS read bandwidth, whole chip */
     double lds_bytes_per_fma; /* LDS bytes read per multiply-add (4: one fp32 operand) */
-    double lane_efficiency;   /* useful fraction of the lanes' multiply-adds */
+    double lane_efficiency;   /* fraction of that ceiling the kernel sustains as useful multiply-adds
+                                 (lanes that are real outputs x issue slots not lost to address
+                                 arithmetic, waits and barriers) */
 } sconv_machine;
 
 typedef struct {

@@ -29,7 +29,19 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    build_ceilings(hipcc)
     return LIB
+
+
+def build_ceilings(hipcc: str) -> str:
+    """The ceilings microbenchmark (stand-alone program, see csrc/sconv_ceilings.hip)."""
+    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_ceilings.py")])
+    exe = os.path.join(HERE, "sconv_ceilings")
+    cmd = [hipcc, "-O3", "-std=c++17", *DEVICE_FLAGS, "-I", CSRC, os.path.join(CSRC, "sconv_ceilings.hip"), "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
+    return exe
 
 
 if __name__ == "__main__":
