@@ -268,6 +268,15 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         const int page4 = a.page_bytes >> 4;
         for (int b = 0; b < a.n_bufs; ++b)
             for (int i = tid; i < page4; i += blockDim.x) z[((b * a.buf_stride_bytes + a.block_bytes) >> 4) + i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        // A read into the right padding of a plane's last row lands on the first `pad` cells of the next
+        // plane.  Staging writes zeros there (left padding), but a last block with fewer than cb channels
+        // leaves the plane after its last channel unwritten: clear those cells of every plane once.
+        const int per_plane = a.pad, total = a.n_bufs * a.cb * per_plane;
+        for (int i = tid; i < total; i += blockDim.x) {
+            const int cell = i % per_plane, pl = i / per_plane;
+            const int b = pl / a.cb, cl = pl - b * a.cb;
+            z[((b * a.buf_stride_bytes + cl * a.plane_bytes) >> 4) + cell] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
 
     const float *in_tile = a.in + (size_t)n0 * CHW;

@@ -86,6 +86,56 @@ def test_every_kernel_shape_on_a_ragged_batch(oracle, plan):
     check(MID, w, x, oracle, plan, what="ragged")
 
 
+BIG = wl.small_layer("big", C=10, H=27, W=27, K=42, R=5, S=5, stride=1, pad=2, groups=2)
+# every accumulator shape (T, R) of the flat-stream kernel: T follows from the band height, R = rows_w
+FLAT_SHAPES = [
+    (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=16, t=1, band=4)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=8, cg=1, rows_w=8, t=2, band=9)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=12, t=2, band=9)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=8, cg=1, rows_w=4, t=3)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=6, t=3)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=8, t=3)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=4, t=4, band=7)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=5, t=4, band=7)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=3, t=5, band=9)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=4, t=5, band=9)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=3, t=6, band=13)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=16, cg=1, rows_w=2, t=7, band=14)),
+    (BIG, dict(kernel=3, nt=4, cb=3, waves=16, cg=1, rows_w=3, t=7, band=14)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=16, cg=2, rows_w=3, t=7, band=27)),
+    (BIG, dict(kernel=3, nt=4, cb=1, waves=16, cg=1, rows_w=1, t=13, band=27)),
+]
+
+
+@pytest.mark.parametrize("case", FLAT_SHAPES, ids=[f"T{p['t']}R{p['rows_w']}cg{p['cg']}" for _, p in FLAT_SHAPES])
+def test_every_flat_stream_shape(oracle, case):
+    layer, plan = case
+    x, w = rand_case(layer, 9, 0.2, seed=61)
+    w[3] = 0                      # an empty row
+    w[layer.K - 1, :, 1:, :] = 0  # a short row
+    _, info = check(layer, w, x, oracle, plan, what="flat-shape")
+    assert {k: info["plan"][k] for k in plan} == plan
+
+
+def test_tiling_follows_the_batch_size(oracle):
+    """One handle, three batch sizes: the library re-plans and re-packs between them."""
+    layer = wl.small_layer("replan", C=24, H=28, W=28, K=64, R=3, S=3, stride=1, pad=1, groups=1)
+    x, w = rand_case(layer, 40, 0.2, seed=63)
+    h = B.sconv_create_csr(layer, w)
+    plans = []
+    for n in (40, 8, 40, 5, 2):
+        xd = torch.from_numpy(x[:n]).cuda()
+        out = torch.full((n, layer.K, layer.OH, layer.OW), float("nan"), device="cuda")
+        B.sconv_forward(h, xd, out)
+        got = out.cpu().numpy()
+        ref, ab, _ = oracle.sparse_conv(layer, w, x[:n])
+        assert np.all(np.abs(got - ref) <= TOL * ab), n
+        plans.append(B.sconv_csr_info(h)["plan"])
+    r, o, v = B.sconv_csr_unpack(h, 1)
+    er, eo, ev = B.sconv_csr_export(h)
+    assert np.array_equal(r, er) and np.array_equal(o, eo) and np.array_equal(v.view(np.uint32), ev.view(np.uint32))
+
+
 SHAPES = [
     dict(C=8, H=27, W=27, K=16, R=5, S=5, stride=1, pad=2, groups=2),
     dict(C=6, H=28, W=28, K=12, R=3, S=3, stride=1, pad=1, groups=1),
