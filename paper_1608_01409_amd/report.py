@@ -4,7 +4,7 @@ roofline model's prediction and the dense-convolution crossover (Section 2.2,
 Section 3.2 / Figure 5 of the paper), the skewed guided-pruning-like patterns,
 and the GoogLeNet-like and strided layers.
 
-    python -m paper_1608_01409_amd.report sweep|skewed|extra|all [--iters K]
+    python -m paper_1608_01409_amd.report sweep|skewed|extra|onebyone|all [--iters K]
 
 Every input is seeded and synthetic (paper_1608_01409_amd/workloads.py).  The
 dense reference is the vendor's fp32 convolution reached through
@@ -137,26 +137,31 @@ def report_skewed(iters):
         emit(row)
 
 
-def report_extra(iters):
-    print("# GoogLeNet-inception-like and strided layers, batch 64 (configuration 5)")
-    for li, (name, N, dens) in enumerate(wl.CONFIGS[4]):
+def report_extra(iters, cfg=4, title="# GoogLeNet-inception-like and strided layers, batch 64 (configuration 5)"):
+    print(title)
+    for li, (name, N, dens) in enumerate(wl.CONFIGS[cfg]):
         layer = wl.LAYERS[name]
-        x, w = wl.make_case(4, li, layer, N, dens)
+        x, w = wl.make_case(cfg, li, layer, N, dens)
         xd = torch.from_numpy(x).cuda()
         ms, info, h = time_sparse(layer, w, xd, iters)
         t_dense = time_dense(layer, xd, iters)
         flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
         pred = B.sconv_model_predict(layer, N, dens, h)
+        hbm = pred["bytes_act"] / (ms * 1e-3) / 1e12
         row = dict(report="extra", layer=name, N=N, density=dens, nnz=info["nnz"], t_us=ms * 1e3, tflops=flops / ms / 1e9,
-                   t_dense_us=t_dense * 1e3, speedup=t_dense / ms, t_model_us=pred["t_sparse"] * 1e6, plan=info["plan"])
-        print(f"{name}: N {N} x {dens} nnz {info['nnz']}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s, dense {t_dense*1e3:.1f} us, "
-              f"speedup {t_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us, plan {info['plan']}")
+                   t_dense_us=t_dense * 1e3, speedup=t_dense / ms, t_model_us=pred["t_sparse"] * 1e6,
+                   model_bandwidth_bound=bool(pred["bandwidth_bound"]), model_x_upper=pred["x_upper"],
+                   model_x_lower=pred["x_lower"], activation_tb_per_s=hbm, plan=info["plan"])
+        print(f"{name}: N {N} x {dens} nnz {info['nnz']}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s "
+              f"({hbm:.2f} TB/s of activations), dense {t_dense*1e3:.1f} us, speedup {t_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us "
+              f"({'bandwidth' if pred['bandwidth_bound'] else 'compute'} bound, useful x in ({pred['x_upper']:.3f}, {pred['x_lower']:.3f})), "
+              f"plan {info['plan']}")
         emit(row)
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["sweep", "skewed", "extra", "all"])
+    ap.add_argument("what", choices=["sweep", "skewed", "extra", "onebyone", "all"])
     ap.add_argument("--iters", type=int, default=20)
     args = ap.parse_args()
     if not torch.cuda.is_available():
@@ -169,6 +174,9 @@ def main() -> int:
         report_skewed(args.iters)
     if args.what in ("extra", "all"):
         report_extra(args.iters)
+    if args.what in ("onebyone", "all"):
+        report_extra(args.iters, 5, "# 1x1 layers of inception modules, batch 64: Section 2.2 predicts no useful sparsity range "
+                                    "when x_upper >= x_lower")
     return 0
 
 

@@ -64,6 +64,10 @@ LAYERS = {
     "conv5": Layer("conv5", 384, 13, 13, 256, 3, 3, 1, 1, 2),
     "goog3x3": Layer("goog3x3", 192, 28, 28, 128, 3, 3, 1, 1, 1),
     "goog5x5": Layer("goog5x5", 32, 28, 28, 96, 5, 5, 1, 2, 1),
+    # 1x1 "reduce" layers of inception modules: few FLOPs per activation byte, the layers for which
+    # Section 2.2 predicts no useful sparsity range
+    "goog1x1_reduce": Layer("goog1x1_reduce", 480, 14, 14, 16, 1, 1, 1, 0, 1),
+    "goog1x1": Layer("goog1x1", 192, 28, 28, 64, 1, 1, 1, 0, 1),
 }
 
 # (layer name, batch, density) per benchmark configuration.
@@ -71,6 +75,7 @@ CONFIGS = {
     0: [("conv3", 1, 0.10)],
     1: [("conv2", 256, 0.10), ("conv3", 256, 0.10), ("conv4", 256, 0.10), ("conv5", 256, 0.10)],
     4: [("goog3x3", 64, 0.20), ("goog5x5", 64, 0.30), ("conv1", 64, 0.30)],
+    5: [("goog1x1_reduce", 64, 0.30), ("goog1x1", 64, 0.30)],   # beyond the benchmark configurations
 }
 SWEEP_DENSITIES = (0.01, 0.02, 0.05, 0.1, 0.2, 0.3, 0.5, 1.0)
 WEIGHT_STD = 0.01

@@ -136,6 +136,31 @@ def test_tiling_follows_the_batch_size(oracle):
     assert np.array_equal(r, er) and np.array_equal(o, eo) and np.array_equal(v.view(np.uint32), ev.view(np.uint32))
 
 
+def _random_layer(rng):
+    groups = int(rng.choice([1, 1, 2, 3]))
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    stride = int(rng.choice([1, 1, 1, 2, 3]))
+    pad = int(rng.integers(0, 4))
+    H = int(rng.integers(max(R - 2 * pad, 1), 31)) + (0 if R - 2 * pad <= 0 else 0)
+    W = int(rng.integers(max(S - 2 * pad, 1), 31))
+    H, W = max(H, R - 2 * pad, 1), max(W, S - 2 * pad, 1)
+    return wl.small_layer("rnd", C=groups * int(rng.integers(1, 9)), H=H, W=W, K=groups * int(rng.integers(1, 20)),
+                          R=R, S=S, stride=stride, pad=pad, groups=groups)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_layers_automatic_plan(oracle, seed):
+    """Seeded random geometry (kernel sizes 1-5, strides 1-3, pads 0-3, groups 1-3, images up to 30x30),
+    random density and batch: whatever the library chooses must match the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    layer = _random_layer(rng)
+    N = int(rng.choice([4, 5, 7, 12, 17]))
+    x, w = rand_case(layer, N, float(rng.choice([0.05, 0.2, 0.5, 1.0])), seed=8000 + seed)
+    if layer.K > 2:
+        w[int(rng.integers(0, layer.K))] = 0
+    check(layer, w, x, oracle, None, what=f"random-{seed}")
+
+
 SHAPES = [
     dict(C=8, H=27, W=27, K=16, R=5, S=5, stride=1, pad=2, groups=2),
     dict(C=6, H=28, W=28, K=12, R=3, S=3, stride=1, pad=1, groups=1),
@@ -254,6 +279,14 @@ def test_config4_googlenet_like_and_strided(oracle, li):
     layer = wl.LAYERS[name]
     x, w = wl.make_case(4, li, layer, N, dens)
     check(layer, w, x, oracle, None, images=[0, 3, 4, 33, 63], what=f"config4-{name}")
+
+
+@pytest.mark.parametrize("li", range(2))
+def test_one_by_one_layers(oracle, li):
+    name, N, dens = wl.CONFIGS[5][li]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(5, li, layer, N, dens)
+    check(layer, w, x, oracle, None, images=[0, 3, 4, 33, 63], what=f"1x1-{name}")
 
 
 @pytest.mark.parametrize("dens", [0.01, 0.5, 1.0])
