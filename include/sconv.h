@@ -175,6 +175,32 @@ void sconv_machine_gfx950(sconv_machine *m);
 int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
                         const sconv_machine *m, sconv_prediction *out);
 
+/* ---- the pruning controller's decision (Section 2.3, the Guided Sparsity Learning algorithm) ---- */
+
+/*
+ * What the algorithm does with one layer, given the model.  Sparsity bounds are
+ * stated as densities here: the "upper bound of the useful sparsity range" is
+ * the density x_upper below which the layer is bandwidth bound and pruning
+ * brings no more speed; the "lower bound" is the density x_lower = 1/alpha
+ * above which the sparse kernel is slower than dense convolution.
+ */
+typedef enum {
+    SCONV_GSL_EXCLUDE = 0,        /* no useful range (x_upper >= x_lower): never prune this layer */
+    SCONV_GSL_PRUNE = 1,          /* inside or above the useful range and still moving: keep pruning */
+    SCONV_GSL_STOP = 2,           /* density <= x_upper: stop pruning, the other layers get the room */
+    SCONV_GSL_RESTORE_DENSE = 3   /* density has stabilised at or above x_lower: stop and restore the dense weights */
+} sconv_gsl_action;
+
+/*
+ * Decide for one layer at batch N with current nonzero density `density`
+ * (in (0, 1]); `stabilized` != 0 says the density has stopped changing.  `m`
+ * NULL = the gfx950 defaults.  *pred (may be NULL) receives the model's
+ * prediction the decision was taken on.  Pure host arithmetic; only the
+ * decision is built here, not the training loop around it.
+ */
+int sconv_gsl_decide(const sconv_desc *desc, int32_t N, double density, int32_t stabilized, const sconv_machine *m,
+                     int32_t *action, sconv_prediction *pred);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,3 +71,19 @@ def predict(layer, N: int, x: float, F: float, B: float, alpha: float, beta: flo
         "x_lower": 1.0 / alpha,
         "bandwidth_bound": t_sbw > t_sc,
     }
+
+
+def gsl_decide(layer, N: int, x: float, stabilized: bool, F: float, B: float, alpha: float, beta: float = 2.0) -> str:
+    """Section 2.3, the algorithm's per-layer rules, with sparsity bounds written as densities:
+    initialise: a layer without speedup potential (empty useful range) is excluded;
+    periodically: sparsity >= upper bound of the useful range -> stop pruning;
+                  stabilised sparsity <= lower bound          -> stop and restore the dense weights;
+    otherwise the layer stays in the pruning set."""
+    p = predict(layer, N, x, F, B, alpha, beta)
+    if not p["x_upper"] < p["x_lower"]:
+        return "exclude"
+    if x <= p["x_upper"]:
+        return "stop"
+    if stabilized and x >= p["x_lower"]:
+        return "restore_dense"
+    return "prune"

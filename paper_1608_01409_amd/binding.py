@@ -44,7 +44,8 @@ class sconv_prediction(C.Structure):
 
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
-           "sconv_machine_gfx950", "sconv_model_predict"]
+           "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide"]
+GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
 class SconvError(RuntimeError):
@@ -76,6 +77,8 @@ def lib():
         L.sconv_machine_gfx950.restype = None
         L.sconv_model_predict.argtypes = [C.POINTER(sconv_desc), i32, C.c_double, vp, C.POINTER(sconv_machine),
                                           C.POINTER(sconv_prediction)]
+        L.sconv_gsl_decide.argtypes = [C.POINTER(sconv_desc), i32, C.c_double, i32, C.POINTER(sconv_machine),
+                                       C.POINTER(i32), C.POINTER(sconv_prediction)]
         _lib = L
     return _lib
 
@@ -211,3 +214,14 @@ def sconv_model_predict(layer, N: int, density: float, csr: Csr | None = None, m
                                      C.byref(machine) if machine is not None else None, C.byref(p)),
            "sconv_model_predict")
     return p.as_dict()
+
+
+def sconv_gsl_decide(layer, N: int, density: float, stabilized: bool = False, machine: sconv_machine | None = None):
+    """(action name, prediction dict) of the pruning controller for one layer."""
+    d = make_desc(layer)
+    act = C.c_int32(-1)
+    p = sconv_prediction()
+    _check(lib().sconv_gsl_decide(C.byref(d), N, float(density), int(bool(stabilized)),
+                                  C.byref(machine) if machine is not None else None, C.byref(act), C.byref(p)),
+           "sconv_gsl_decide")
+    return GSL_ACTIONS[act.value], p.as_dict()

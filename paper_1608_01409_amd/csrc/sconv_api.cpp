@@ -368,3 +368,27 @@ extern "C" int sconv_model_predict(const sconv_desc *desc, int32_t N, double den
     *out = p;
     return SCONV_OK;
 }
+
+// Section 2.3's algorithm, one layer, one decision: exclude layers without a useful sparsity range at the
+// start; stop pruning a layer once its sparsity reaches the upper bound of the range (density <= x_upper);
+// give up on a layer whose sparsity has stabilised at or below the lower bound (density >= x_lower) and
+// restore its dense weights; otherwise keep pruning.
+extern "C" int sconv_gsl_decide(const sconv_desc *desc, int32_t N, double density, int32_t stabilized,
+                                const sconv_machine *m, int32_t *action, sconv_prediction *pred)
+{
+    if (!action) return SCONV_ERR_NULL;
+    if (!(density > 0.0) || density > 1.0) return SCONV_ERR_DESC;
+    sconv_prediction p;
+    const int rc = sconv_model_predict(desc, N, density, nullptr, m, &p);
+    if (rc) return rc;
+    if (pred) *pred = p;
+    if (!(p.x_upper < p.x_lower))
+        *action = SCONV_GSL_EXCLUDE;
+    else if (density <= p.x_upper)
+        *action = SCONV_GSL_STOP;
+    else if (stabilized && density >= p.x_lower)
+        *action = SCONV_GSL_RESTORE_DENSE;
+    else
+        *action = SCONV_GSL_PRUNE;
+    return SCONV_OK;
+}

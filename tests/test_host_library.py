@@ -225,3 +225,25 @@ def test_model_derived_alpha_and_realised_density():
     d = B.make_desc(layer)
     assert L.sconv_model_predict(C.byref(d), 0, 0.1, None, None, C.byref(p)) == B.ERR["BATCH"]
     assert L.sconv_model_predict(C.byref(d), 1, 0.1, None, None, None) == B.ERR["NULL"]
+
+
+def test_gsl_decision_matches_oracle():
+    cases = [(2150e9, 122e9, 3.0), (62e9, 15e9, 1.2)]
+    for name in ("conv5", "conv2", "goog1x1_reduce", "goog1x1", "goog3x3"):
+        layer = wl.LAYERS[name]
+        for (F, Bw, alpha) in cases:
+            m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0)
+            for N in (1, 64):
+                for x in (0.004, 0.015, 0.05, 0.2, 0.34, 0.9, 1.0):
+                    for st in (False, True):
+                        act, pred = B.sconv_gsl_decide(layer, N, x, st, m)
+                        assert act == pm.gsl_decide(layer, N, x, st, F, Bw, alpha), (name, F, N, x, st)
+                        assert math.isclose(pred["x_lower"], 1 / alpha)
+    # gfx950 defaults: the AlexNet layers have a useful range, the 1x1 reduce layer has none
+    assert B.sconv_gsl_decide(wl.LAYERS["conv3"], 256, 0.1)[0] == "prune"
+    assert B.sconv_gsl_decide(wl.LAYERS["goog1x1_reduce"], 64, 0.3)[0] == "exclude"
+    L = B.lib()
+    d = B.make_desc(wl.LAYERS["conv3"])
+    a = C.c_int32()
+    assert L.sconv_gsl_decide(C.byref(d), 1, 0.0, 0, None, C.byref(a), None) == B.ERR["DESC"]
+    assert L.sconv_gsl_decide(C.byref(d), 1, 0.5, 0, None, None, None) == B.ERR["NULL"]

@@ -77,3 +77,23 @@ def test_derived_alpha():
     assert math.isclose(a, 100e12 / (0.8 * 40e12))
     a = pm.derive_alpha(F=100e12, fma_flops=30e12, lds_bytes_per_s=80e12, lds_bytes_per_fma=4.0, lane_efficiency=1.0)
     assert math.isclose(a, 100 / 30)
+
+
+def test_gsl_rules_on_the_papers_examples():
+    """Section 2.3: the 1x1 reduce layer that is bandwidth bound before pruning is excluded; conv5 is pruned
+    inside its useful range, stopped below x_upper (~0.02 on the Xeon) and given up above 1/alpha = 0.3."""
+    F, B, a = GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"]
+    reduce_ = wl.LAYERS["goog1x1_reduce"]
+    dense = pm.predict(reduce_, 1, 1.0, F, B, 1.0)
+    assert dense["t_dense"] < dense["t_sparse_bw"]            # bandwidth bound even when dense
+    assert (pm.gsl_decide(reduce_, 1, 0.3, False, F, B, a) != "exclude") == bool(GOLD["inception_4a_5x5_reduce_has_potential"])
+    assert (pm.gsl_decide(CONV5, 1, 0.3, False, F, B, a) != "exclude") == bool(GOLD["alexnet_conv5_has_potential"])
+    assert pm.gsl_decide(CONV5, 1, 0.10, False, F, B, a) == "prune"
+    assert pm.gsl_decide(CONV5, 1, 0.10, True, F, B, a) == "prune"       # stabilised inside the range: keep it sparse
+    assert pm.gsl_decide(CONV5, 1, 0.015, False, F, B, a) == "stop"      # below x_upper ~ 0.02
+    assert pm.gsl_decide(CONV5, 1, 0.5, False, F, B, a) == "prune"       # still moving
+    assert pm.gsl_decide(CONV5, 1, 0.5, True, F, B, a) == "restore_dense"  # stuck above 1/alpha ~ 0.33
+    # the decision is monotone in the density once stabilised: stop, prune, restore
+    order = {"stop": 0, "prune": 1, "restore_dense": 2}
+    seq = [order[pm.gsl_decide(CONV5, 1, x, True, F, B, a)] for x in (0.005, 0.01, 0.03, 0.1, 0.3, 0.34, 0.6, 1.0)]
+    assert seq == sorted(seq) and seq[0] == 0 and seq[-1] == 2
