@@ -8,7 +8,8 @@ through the VGPR index mode (s_set_gpr_idx_on): the row an entry of the nonzero 
 data, not code, so the rows of a wave share one stream with no per-row padding.
 
   stream   per (wave slot, channel block): chunks of 8 entries of 8 bytes,
-           word0 = fp32 weight, word1 = (LDS byte offset << 8) | (row * T * 4).
+           word0 = fp32 weight, word1 = (LDS byte offset / 16) << 16 | (row * T * 4): the read address
+           is one v_mad_u32_u16 (high half x 16 + lane base), the accumulator index is the low byte.
            Three chunk buffers A (in use), B (next, valid), N (loading); the loop body is unrolled
            three times with the names rotated, so no register moves are needed.
   reads    entry p reads T float4 at lane_base + offset + t*1024 (ds_read_b128); the reads of entry
@@ -126,14 +127,12 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
         emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
         if batch:
             for j in range(CH):
-                emit(f"s_lshr_b32 s{STMP}, {entry_w1(j + D)}, 8")
-                emit(f"v_add_u32 v{VA0 + j}, s{STMP}, v{VLB}")
+                emit(f"v_mad_u32_u16 v{VA0 + j}, {entry_w1(j + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
         for u in range(CH):
             slot = u % D
             va = VA0 + (u if batch else slot)
             if not batch:
-                emit(f"s_lshr_b32 s{STMP}, {entry_w1(u + D)}, 8")
-                emit(f"v_add_u32 v{va}, s{STMP}, v{VLB}")
+                emit(f"v_mad_u32_u16 v{va}, {entry_w1(u + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
             emit(f"s_set_gpr_idx_on {w1(A, u)}, gpr_idx(DST)")
             for t in range(T):
                 emit(f"s_waitcnt lgkmcnt({D * T - 1})")
@@ -196,8 +195,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
     emit(f"s_add_u32 s{STMP}, s{SBUF}, {OP['ldsbase']}")
     emit(f"v_add_u32 v{VLB}, s{STMP}, {OP['lane_byte']}")
     for d in range(D):
-        emit(f"s_lshr_b32 s{STMP}, {w1(SA, d)}, 8")
-        emit(f"v_add_u32 v{VA0 + d}, s{STMP}, v{VLB}")
+        emit(f"v_mad_u32_u16 v{VA0 + d}, {w1(SA, d)}, 16, v{VLB} op_sel:[1,0,0,0]")
         for t in range(T):
             emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * 1024}")
     emit(f"{noreads}:")

@@ -428,14 +428,14 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
 {
     const Geometry g = geometry(d);
     const int rows_w = t.p.rows_w, cb = t.p.cb;
-    if (t.p.nt != 4 || rows_w * t.p.t * 4 > 256 || t.zero_page >= (1u << 24)) return SCONV_ERR_PLAN;
+    if (t.p.nt != 4 || rows_w * t.p.t * 4 > 256 || t.zero_page >= (1u << 20) || t.zero_page % 16) return SCONV_ERR_PLAN;
     out.t = t;
     int rc = deal_rows(d, c, t, out.row_of);
     if (rc) return rc;
     out.seg.assign((size_t)t.wave_slots * t.nblk * 2 + 2, 0); // one spare entry: the kernel looks one block ahead
     out.pairs.clear();
     out.pairs.reserve(c.val.size() + (size_t)t.wave_slots * t.nblk * 4);
-    const uint64_t pad_entry = (uint64_t)(t.zero_page << 8) << 32;
+    const uint64_t pad_entry = (uint64_t)((t.zero_page / 16) << 16) << 32;
     size_t real = 0;
     // nonzeros of a row by block: walk each row once per slot, bucketing by channel block
     std::vector<std::vector<uint64_t>> bucket(t.nblk);
@@ -454,13 +454,13 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
                 if (byte_off >= t.zero_page) return SCONV_ERR_PLAN;
                 uint32_t vb;
                 std::memcpy(&vb, &c.val[j], 4);
-                bucket[b].push_back((uint64_t)vb | ((uint64_t)((byte_off << 8) | (uint32_t)(i * t.p.t * 4)) << 32));
+                bucket[b].push_back((uint64_t)vb | ((uint64_t)(((byte_off / 16) << 16) | (uint32_t)(i * t.p.t * 4)) << 32));
                 ++real;
             }
         }
         for (int b = 0; b < t.nblk; ++b) {
             // entries in ascending LDS offset: rows that share a column sit next to each other
-            std::stable_sort(bucket[b].begin(), bucket[b].end(), [](uint64_t x, uint64_t y) { return (x >> 40) < (y >> 40); });
+            std::stable_sort(bucket[b].begin(), bucket[b].end(), [](uint64_t x, uint64_t y) { return (x >> 48) < (y >> 48); });
             const size_t start = out.pairs.size();
             out.pairs.insert(out.pairs.end(), bucket[b].begin(), bucket[b].end());
             while ((out.pairs.size() - start) % SCONV_FLAT_CHUNK) out.pairs.push_back(pad_entry);
@@ -550,9 +550,9 @@ int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out)
             for (size_t j = start; j < start + n; ++j) {
                 const uint32_t vb = (uint32_t)(p.pairs[j] & 0xffffffffu);
                 const uint32_t w1 = (uint32_t)(p.pairs[j] >> 32);
-                const uint32_t byte_off = w1 >> 8;
+                const uint32_t byte_off = (w1 >> 16) * 16;
                 if (byte_off >= t.zero_page) continue; // chunk padding
-                const int i = (int)(w1 & 0xffu) / (t.p.t * 4);
+                const int i = (int)(w1 & 0xffffu) / (t.p.t * 4);
                 if (i >= rows_w) return SCONV_ERR_CSR;
                 const int k = p.row_of[(size_t)ws * rows_w + i];
                 if (k < 0) return SCONV_ERR_CSR;

@@ -72,7 +72,7 @@ struct PackedLds {
 // Packing for the flat-stream kernel (tiles of 4 images).  One stream per (wave slot, channel block)
 // holding the nonzeros of all rows of the slot in that block, padded to whole chunks of 8 entries:
 //   low 32 bits  fp32 value bits
-//   high 32 bits (LDS byte offset << 8) | (row index inside the slot * t * 4)
+//   high 32 bits (LDS byte offset / 16) << 16 | (row index inside the slot * t * 4)
 // Padding entries have value +0.0 and point at the zero page.
 #define SCONV_FLAT_CHUNK 8
 struct PackedFlat {
