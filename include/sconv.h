@@ -59,10 +59,14 @@ typedef struct {
  * 4), a band of `band` consecutive output rows (0 = choose; OH = the whole
  * image) and `waves/cg * rows_w` CSR rows; it walks the input channels in
  * blocks of `cb`; each wave keeps rows_w x t x (4 if nt >= 4 else 1)
- * accumulators per lane.
+ * accumulators per lane.  `strip` (kernel 3 only): 0 = the lanes of a wave
+ * span 64 consecutive cells of the padded plane, chunk after chunk; w > 0 =
+ * they span a block of 64/w output rows by w output columns and the t chunks of
+ * a wave are t such blocks side by side (t*w >= OW, band <= cg * (64/w)),
+ * which wastes fewer lanes when OW is a little under t*w.
  */
 typedef struct {
-    int32_t kernel, nt, cb, waves, cg, rows_w, t, band;
+    int32_t kernel, nt, cb, waves, cg, rows_w, t, band, strip;
 } sconv_plan;
 
 typedef struct sconv_csr sconv_csr; /* opaque, owned by the library */

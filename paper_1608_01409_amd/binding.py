@@ -21,7 +21,7 @@ class sconv_desc(C.Structure):
 
 
 class sconv_plan(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("kernel", "nt", "cb", "waves", "cg", "rows_w", "t", "band")]
+    _fields_ = [(n, C.c_int32) for n in ("kernel", "nt", "cb", "waves", "cg", "rows_w", "t", "band", "strip")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -12,7 +12,7 @@ data, not code, so the rows of a wave share one stream with no per-row padding.
            is one v_mad_u32_u16 (high half x 16 + lane base), the accumulator index is the low byte.
            Three chunk buffers A (in use), B (next, valid), N (loading); the loop body is unrolled
            three times with the names rotated, so no register moves are needed.
-  reads    entry p reads T float4 at lane_base + offset + t*1024 (ds_read_b128); the reads of entry
+  reads    entry p reads T float4 at lane_base + offset + t*step*16 (ds_read_b128); the reads of entry
            p + D are issued while entry p is multiplied (ring of D*T float4).  LDS returns in order,
            so the oldest read is complete once lgkmcnt <= D*T - 1; the scalar load of chunk N only
            makes that wait stricter, and lgkmcnt(0) at the end of a chunk makes N valid.
@@ -28,12 +28,17 @@ from __future__ import annotations
 import os
 import sys
 
-# (T, R, D, batch): batch = compute the 8 read addresses of a chunk at once (8 address VGPRs) instead of
-# one at a time with the index mode toggled off and on around each (D address VGPRs, for shapes short of VGPRs)
+# (T, R, D, batch, step): batch = compute the 8 read addresses of a chunk at once (8 address VGPRs) instead of
+# one at a time with the index mode toggled off and on around each (D address VGPRs, for shapes short of VGPRs);
+# step = LDS cells between the reads of consecutive chunks of one lane: 64 when the lanes of a wave span 64
+# consecutive cells of the plane (chunk t = the next 64 cells), w when they span a block of 64/w rows by w
+# columns (chunk t = the same rows, the next w columns).  The step is an immediate of the read instruction.
 SHAPES = [
-    (1, 16, 4, True), (2, 8, 4, True), (2, 12, 1, True), (3, 4, 4, True), (3, 6, 2, True), (3, 8, 1, True),
-    (4, 4, 2, True), (4, 5, 1, True), (5, 3, 2, True), (5, 4, 1, True), (6, 3, 1, True), (7, 2, 2, False),
-    (7, 3, 1, False), (13, 1, 1, False),
+    (1, 16, 4, True, 64), (2, 8, 4, True, 64), (2, 12, 1, True, 64), (3, 4, 4, True, 64), (3, 6, 2, True, 64),
+    (3, 8, 1, True, 64), (4, 4, 2, True, 64), (4, 5, 1, True, 64), (5, 3, 2, True, 64), (5, 4, 1, True, 64),
+    (6, 3, 1, True, 64), (7, 2, 2, False, 64), (7, 3, 1, False, 64), (13, 1, 1, False, 64),
+    (3, 4, 4, True, 9), (3, 6, 2, True, 9), (3, 8, 1, True, 9),            # 27 columns in 3 strips of 9
+    (7, 2, 2, False, 8), (7, 3, 1, False, 8),                              # 55 or 56 columns in 7 strips of 8
 ]
 CH = 8                      # entries per chunk
 W = 2 * CH                  # dwords per chunk
@@ -57,7 +62,7 @@ OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase"
 OP = {n: f"%{i}" for i, n in enumerate(OPS)}
 
 
-def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
+def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     assert CH % D == 0 and R * T * 4 <= 256
     nacc = R * T * 4
     ring_regs = D * T * 4
@@ -138,7 +143,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
                 emit(f"s_waitcnt lgkmcnt({D * T - 1})")
                 for e in range(4):
                     emit(f"v_fmac_f32 v{ACC0 + t * 4 + e}, {w0(A, u)}, {q(slot, t, e)}")
-                emit(f"ds_read_b128 {q(slot, t)}, v{va} offset:{t * 1024}")
+                emit(f"ds_read_b128 {q(slot, t)}, v{va} offset:{t * step * 16}")
             if not batch:
                 emit("s_set_gpr_idx_off")
         if batch:
@@ -197,7 +202,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
     for d in range(D):
         emit(f"v_mad_u32_u16 v{VA0 + d}, {w1(SA, d)}, 16, v{VLB} op_sel:[1,0,0,0]")
         for t in range(T):
-            emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * 1024}")
+            emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * step * 16}")
     emit(f"{noreads}:")
     emit(f"s_add_u32 s{STMP}, s{SBLK}, 1")
     emit(f"s_cmp_ge_u32 s{STMP}, s{SNBLK}")
@@ -281,7 +286,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool) -> str:
     clob += ['"vcc"', '"scc"', '"memory"']
     return f"""
 template <>
-struct Lds2Asm<{T}, {R}> {{
+struct Lds2Asm<{T}, {R}, {step}> {{
     static constexpr int kDepth = {D};
     static __device__ __forceinline__ void run(unsigned long long kern, int4v rsrc, const unsigned *segp, const int *rowp,
                                                unsigned outp_lo, unsigned outp_hi, unsigned soff0, unsigned nimg,
@@ -301,10 +306,10 @@ struct Lds2Asm<{T}, {R}> {{
 
 def generate() -> str:
     parts = ["// GENERATED by gen_lds2.py -- do not edit; edit the generator and rebuild.\n",
-             "template <int T, int R>\nstruct Lds2Asm;\n"]
+             "template <int T, int R, int STEP>\nstruct Lds2Asm;\n"]
     for s in SHAPES:
         parts.append(gen_shape(*s))
-    parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r})" for t, r, _, _ in SHAPES) + "\n")
+    parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r}, {st})" for t, r, _, _, st in SHAPES) + "\n")
     parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
                  f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")
     return "".join(parts)

@@ -92,10 +92,15 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Row pitch of the LDS plane.  W + pad columns are enough for the reads: one that runs into the right
 // padding of a row (X >= W + pad) lands on column X - pitch < pad of the next row, left padding, zero as
 // well.  The pitch must also hold a whole output row, which is wider than that when pad > S - 1.
-static int lds_pitch(const sconv_desc &d)
+// With strips, lane l of a chunk sits on cell (l / strip) * pitch + l % strip; a pitch congruent to the strip
+// width modulo 16 makes that congruent to l, so that the 64 lanes of a 16-byte read fall on the LDS banks
+// exactly as 64 consecutive cells do (the natural pitch costs a third of the read rate in bank conflicts).
+static int lds_pitch(const sconv_desc &d, int strip = 0)
 {
     const Geometry g = geometry(d);
-    return std::max(d.W + d.pad, g.OW);
+    int pitch = std::max(d.W + d.pad, g.OW);
+    while (strip && (pitch - strip) % 16) ++pitch;
+    return pitch;
 }
 
 static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
@@ -109,20 +114,28 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     if (p.kernel != 3) t.p.kernel = 1;
     t.vec = (p.nt % 4 == 0) ? 4 : 1;
     if ((64 * t.vec) % p.nt) return SCONV_ERR_PLAN;
+    if (p.strip < 0 || p.strip > 64 || (p.strip && t.p.kernel != 3)) return SCONV_ERR_PLAN;
     if (t.p.kernel == 3) {
-        if (p.nt != 4 || !lds2_kernel_available(p.t, p.rows_w)) return SCONV_ERR_PLAN;
+        if (p.nt != 4 || !lds2_kernel_available(p.t, p.rows_w, p.strip ? p.strip : 64)) return SCONV_ERR_PLAN;
     } else if (!lds_kernel_available(t.vec, p.t, p.rows_w)) {
         return SCONV_ERR_PLAN;
     }
-    if (t.p.band == 0) t.p.band = g.OH;
+    t.strip_rows = p.strip ? 64 / p.strip : 0;
+    if (t.p.band == 0) t.p.band = p.strip ? std::min(g.OH, p.cg * t.strip_rows) : g.OH;
     t.n_bands = ceil_div(g.OH, t.p.band);
-    t.Wl = lds_pitch(d);
+    t.Wl = lds_pitch(d, p.strip);
     t.Hl = t.p.band + d.R - 1;
     t.plane_cells = t.Hl * t.Wl;
     t.pos_span = (t.p.band - 1) * t.Wl + g.OW;
     t.pos_per_chunk = 64 * t.vec / p.nt;
     t.n_chunks = ceil_div(t.pos_span, t.pos_per_chunk);
-    if (t.n_chunks > p.cg * p.t) return SCONV_ERR_PLAN;
+    if (p.strip) {
+        // t strips of `strip` columns cover the width, cg blocks of strip_rows rows the band
+        if (p.t * p.strip < g.OW || t.p.band > p.cg * t.strip_rows) return SCONV_ERR_PLAN;
+        t.n_chunks = p.cg * p.t;
+    } else if (t.n_chunks > p.cg * p.t) {
+        return SCONV_ERR_PLAN;
+    }
     if (p.cb > g.Cg) t.p.cb = g.Cg;
     t.nblk = ceil_div(g.Cg, t.p.cb);
     t.rg = p.waves / p.cg;
@@ -132,13 +145,16 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     const int plane_floats = t.plane_cells * p.nt;
     t.n_slabs = ceil_div(plane_floats, 64);
     if (ceil_div(t.n_slabs, p.waves) > 4) return SCONV_ERR_PLAN; // slabs one wave stages per channel
-    // LDS layout in floats: n_bufs x { [block: cb*plane_cells*nt] [zero page: cg*t*64*vec] }.  The zero
+    // LDS layout in floats: n_bufs x { [block: cb*plane_cells*nt] [zero page] }.  The zero
     // pages are cleared once per launch and never written.  A page serves three readers of the block in
     // front of it: the right padding of the very last row (pad*nt floats past the block), lanes past the
     // last valid position (their results are dropped), and the padding entries of the nonzero stream,
-    // whose offset is the page's start, so that they multiply 0 by 0 for every lane and chunk.
+    // whose offset is the page's start, so that they multiply 0 by 0 for every lane and chunk: the page
+    // has one cell more than the farthest cell a lane's chunk can start on (flat lanes: cg*t*64 cells;
+    // strips: last row of the band, last column of the last strip).
     const int64_t block = (int64_t)t.p.cb * plane_floats;
-    const int64_t page = (int64_t)p.cg * p.t * 64 * t.vec;
+    t.page_cells = p.strip ? (t.p.band - 1) * t.Wl + p.t * p.strip : p.cg * p.t * 64 * t.vec / p.nt;
+    const int64_t page = (int64_t)t.page_cells * p.nt;
     if (page < (int64_t)d.pad * p.nt) return SCONV_ERR_PLAN;
     const int64_t stride = (block + page + 3) / 4 * 4;
     t.n_bufs = t.nblk > 1 ? 2 : 1;
@@ -224,7 +240,7 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
     const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
     double eff = wps >= 4 ? 0.78 : wps >= 3 ? 0.72 : wps >= 2 ? 0.68 : 0.42;
-    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.92; // shallow read-ahead ring
+    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.86; // shallow read-ahead ring
     const double simd_clk = t.p.waves * entries * (4.0 * t.p.t + 1.7); // VALU clocks per SIMD, one workgroup
     double group = m * simd_clk / eff + t.nblk * 1500.0 + 14000.0;
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
@@ -237,6 +253,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
     if (d.stride != 1) return SCONV_ERR_PLAN;
     const bool full = req.nt && req.cb && req.waves && req.cg && req.rows_w && req.t;
     if (full) return fill_tiling(d, req, out);
+    if (req.strip && req.kernel && req.kernel != 3) return SCONV_ERR_PLAN;
     const int kinds[2] = {3, 1};
 
     double best = -1;
@@ -244,7 +261,50 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
     const int nts_small[] = {1, 2};
     const int *nts = N_hint >= 4 ? nts_big : nts_small;
     const int n_nts = N_hint >= 4 ? 3 : 2;
-    const int Wl = lds_pitch(d);
+    // every (waves, rows_w, cb) for one choice of image tile, band, column group, chunk count and lane layout
+    auto try_shapes = [&](int nt, int vec, int band, int cg, int T, int strip) {
+        const int Wl = lds_pitch(d, strip);
+        for (int waves : {4, 8, 16}) {
+            if (req.waves && req.waves != waves) continue;
+            if (waves % cg) continue;
+            for (int ki = 0; ki < 2; ++ki)
+            for (int rows_w = 1; rows_w <= 24; ++rows_w) {
+                const int kind = kinds[ki];
+                if (req.kernel && req.kernel != kind) continue;
+                if (strip && kind != 3) continue;
+                // left to itself the library uses flat streams for tiles of 4 images and per-row
+                // streams only for the small-batch tiles the flat kernel does not cover
+                if (!req.kernel && (kind == 3) != (nt == 4)) continue;
+                if (kind == 3 ? (nt != 4 || !lds2_kernel_available(T, rows_w, strip ? strip : 64))
+                              : !lds_kernel_available(vec, T, rows_w))
+                    continue;
+                if (req.rows_w && req.rows_w != rows_w) continue;
+                for (int wpc_target : {1, 2, 4}) {
+                    if (waves * wpc_target > 16) continue;
+                    const int budget = 160 * 1024 / wpc_target - 256;
+                    const int64_t per_ch = (int64_t)(band + d.R - 1) * Wl * nt * 4;
+                    const int64_t page_cells = strip ? (band - 1) * Wl + T * strip : cg * T * 64 * vec / nt;
+                    const int64_t fixed = page_cells * nt * 4 + 16;
+                    int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
+                    if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
+                    if (req.cb) cb = req.cb;
+                    if (cb < 1) continue;
+                    // even out the blocks
+                    if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
+                    sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip};
+                    LdsTiling t;
+                    if (fill_tiling(d, p, t) != SCONV_OK) continue;
+                    const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
+                                               : tiling_cost(d, t, N_hint, avg_row_nnz);
+                    if (best < 0 || c < best) {
+                        best = c;
+                        out = t;
+                    }
+                }
+            }
+        }
+    };
+
     for (int a = 0; a < n_nts; ++a) {
         const int nt = nts[a];
         if (req.nt && req.nt != nt) continue;
@@ -252,54 +312,33 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
         if (nt > 1 && nt > N_hint) continue;
         const int vec = nt % 4 == 0 ? 4 : 1;
         int last_band = 0;
-        for (int nb = 1; nb <= 8 && nb <= g.OH; ++nb) {
+        for (int nb = 1; nb <= 8 && nb <= g.OH && !req.strip; ++nb) {
             const int band = req.band ? req.band : ceil_div(g.OH, nb);
             if (band == last_band) continue; // same band height as the previous count
             last_band = band;
-            const int pos_span = (band - 1) * Wl + g.OW;
+            const int pos_span = (band - 1) * lds_pitch(d) + g.OW;
             const int n_chunks = ceil_div(pos_span, 64 * vec / nt);
-            for (int waves : {4, 8, 16}) {
-                if (req.waves && req.waves != waves) continue;
-                for (int cg = 1; cg <= 4; ++cg) {
-                    if (waves % cg) continue;
-                    if (req.cg && req.cg != cg) continue;
-                    const int T = ceil_div(n_chunks, cg);
-                    if (req.t && req.t != T) continue;
-                    for (int ki = 0; ki < 2; ++ki)
-                    for (int rows_w = 1; rows_w <= 24; ++rows_w) {
-                        const int kind = kinds[ki];
-                        if (req.kernel && req.kernel != kind) continue;
-                        // left to itself the library uses flat streams for tiles of 4 images and per-row
-                        // streams only for the small-batch tiles the flat kernel does not cover
-                        if (!req.kernel && (kind == 3) != (nt == 4)) continue;
-                        if (kind == 3 ? (nt != 4 || !lds2_kernel_available(T, rows_w)) : !lds_kernel_available(vec, T, rows_w))
-                            continue;
-                        if (req.rows_w && req.rows_w != rows_w) continue;
-                        for (int wpc_target : {1, 2, 4}) {
-                            if (waves * wpc_target > 16) continue;
-                            const int budget = 160 * 1024 / wpc_target - 256;
-                            const int64_t per_ch = (int64_t)(band + d.R - 1) * Wl * nt * 4;
-                            const int64_t fixed = (int64_t)cg * T * 64 * vec * 4 + 16;
-                            int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
-                            if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
-                            if (req.cb) cb = req.cb;
-                            if (cb < 1) continue;
-                            // even out the blocks
-                            if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
-                            sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band};
-                            LdsTiling t;
-                            if (fill_tiling(d, p, t) != SCONV_OK) continue;
-                            const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
-                                                       : tiling_cost(d, t, N_hint, avg_row_nnz);
-                            if (best < 0 || c < best) {
-                                best = c;
-                                out = t;
-                            }
-                        }
-                    }
-                }
+            for (int cg = 1; cg <= 4; ++cg) {
+                if (req.cg && req.cg != cg) continue;
+                const int T = ceil_div(n_chunks, cg);
+                if (req.t && req.t != T) continue;
+                try_shapes(nt, vec, band, cg, T, 0);
             }
             if (req.band) break;
+        }
+        // strips: t blocks of (64 / strip) rows x strip columns side by side, cg such rows of blocks
+        if (nt != 4) continue;
+        for (int strip : {7, 8, 9}) {
+            if (req.strip && req.strip != strip) continue;
+            const int T = ceil_div(g.OW, strip), bh = 64 / strip;
+            if (req.t && req.t != T) continue;
+            for (int cg = 1; cg <= 4; ++cg) {
+                if (req.cg && req.cg != cg) continue;
+                const int nb = ceil_div(g.OH, cg * bh);
+                const int band = req.band ? req.band : ceil_div(g.OH, nb);
+                if (band > cg * bh) continue;
+                try_shapes(nt, vec, band, cg, T, strip);
+            }
         }
     }
     return best < 0 ? SCONV_ERR_PLAN : SCONV_OK;
@@ -476,7 +515,13 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
     const int npos = t.p.cg * t.p.t * 64;
     out.store_tbl.assign(npos, -1);
     for (int pos = 0; pos < npos; ++pos) {
-        const int by = pos / t.Wl, ox = pos % t.Wl;
+        int by = pos / t.Wl, ox = pos % t.Wl;
+        if (t.p.strip) { // [wave of the column group][chunk = strip][lane = row * strip + column]
+            const int cgi = pos / (t.p.t * 64), ch = pos / 64 % t.p.t, lane = pos % 64;
+            const int br = lane / t.p.strip;
+            by = br < t.strip_rows ? cgi * t.strip_rows + br : t.p.band;
+            ox = ch * t.p.strip + lane % t.p.strip;
+        }
         if (by < t.p.band && ox < g.OW) out.store_tbl[pos] = (by * g.OW + ox) * 4;
     }
     return SCONV_OK;

@@ -60,6 +60,8 @@ struct LdsTiling {
     int buf_stride_floats; // floats from one buffer to the next: block + zero page, multiple of 4
     int lds_bytes;      // dynamic LDS per workgroup
     unsigned zero_page; // byte offset, relative to a buffer, of its all-zero page (padding entries)
+    int page_cells;     // size of that page in cells of nt floats
+    int strip_rows;     // strip layout: rows of the block of positions one chunk covers (64 / strip), else 0
 };
 
 struct PackedLds {
@@ -108,7 +110,7 @@ int pack_lds(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packed
 int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out);
 int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedFlat &out);
 int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out);
-bool lds2_kernel_available(int t, int rows_w);
+bool lds2_kernel_available(int t, int rows_w, int step); // step: 64 (flat lanes) or the strip width
 int lds2_depth(int t, int rows_w); // read-ahead depth of a flat-stream shape, 0 if there is none
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
 int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);

@@ -209,6 +209,7 @@ struct Lds2Args {
     int N, C, H, W, K, OH, OW, pad;
     int rg, cg, nkt, band, n_bands, Wl, plane_floats, n_slabs;
     int n_tiles, units, block_bytes, page_bytes, n_bufs;
+    int strip, strip_rows;   // lanes of a wave span strip_rows x strip cells of the plane (0: 64 consecutive cells)
 };
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -223,7 +224,7 @@ static_assert(offsetof(Lds2Args, img_stride_bytes) == SCONV_LDS2_OFF_CONSTS + 28
 constexpr unsigned kSkipLane = 0xFFFFFFFFu; // lane past the end of a plane: writes nothing
 constexpr unsigned kZeroLane = 0x80000000u; // padding cell: beyond num_records, the load returns 0
 
-template <int T, int R>
+template <int T, int R, int STEP>
 __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
 {
     extern __shared__ float4 smem4[];
@@ -289,12 +290,21 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     const unsigned long long op = (unsigned long long)(a.out + ((size_t)n0 * a.K * a.OH + y0) * a.OW);
     const unsigned lim = (unsigned)(min(a.band, a.OH - y0) * a.OW * 4);
     const unsigned ldsbase = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void *)smem4;
-    Lds2Asm<T, R>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc, a.seg + (size_t)wslot * a.nblk * 2,
+    // cell of the plane this lane's chunk 0 sits on; chunk t is STEP cells further.  Flat: position p is
+    // cell p.  Strips: lane = row * strip + column of a block of strip_rows x strip cells, the waves of a
+    // column group stacked vertically; lanes outside the block or the band read cell 0 and store nothing.
+    int cell0 = cgi * T * 64 + lane;
+    if (STEP != 64) {
+        const int by = lane / a.strip, bx = lane - by * a.strip;
+        const int y = cgi * a.strip_rows + by;
+        cell0 = (by < a.strip_rows && y < a.band) ? y * a.Wl + bx : 0;
+    }
+    Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc, a.seg + (size_t)wslot * a.nblk * 2,
                        a.row_of + (size_t)wslot * R,
                        __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
                        (unsigned)__builtin_amdgcn_readfirstlane(g * a.Cg * HW * 4), (unsigned)nimg, lim,
                        __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)(wave * 256), (unsigned)(n_waves * 256),
-                       (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)((cgi * T * 64 + lane) * 16), voff[0],
+                       (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)(cell0 * 16), voff[0],
                        voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4));
 }
 
@@ -427,10 +437,10 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
     return SCONV_ERR_PLAN;
 }
 
-template <int T, int R>
+template <int T, int R, int STEP>
 static int launch_lds2_inst(const Lds2Args &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
 {
-    auto kern = sconv_lds2_kernel<T, R>;
+    auto kern = sconv_lds2_kernel<T, R, STEP>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -449,9 +459,9 @@ static int launch_lds2_inst(const Lds2Args &a, int grid, int threads, int lds_by
     return SCONV_OK;
 }
 
-bool lds2_kernel_available(int t, int rows_w)
+bool lds2_kernel_available(int t, int rows_w, int step)
 {
-#define X(TT, RW) if (t == TT && rows_w == RW) return true;
+#define X(TT, RW, ST) if (t == TT && rows_w == RW && step == ST) return true;
     SCONV_LDS2_SHAPES(X)
 #undef X
     return false;
@@ -459,7 +469,7 @@ bool lds2_kernel_available(int t, int rows_w)
 
 int lds2_depth(int t, int rows_w)
 {
-#define X(TT, RW) if (t == TT && rows_w == RW) return Lds2Asm<TT, RW>::kDepth;
+#define X(TT, RW, ST) if (t == TT && rows_w == RW && ST == 64) return Lds2Asm<TT, RW, ST>::kDepth;
     SCONV_LDS2_SHAPES(X)
 #undef X
     return 0;
@@ -485,7 +495,8 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     a.n_tiles = (N + 3) / 4;
     a.units = d.groups * t.nkt * t.n_bands;
     a.block_bytes = (int)t.zero_page;
-    a.page_bytes = t.p.cg * t.p.t * 1024;
+    a.page_bytes = t.page_cells * 16;
+    a.strip = t.p.strip; a.strip_rows = t.strip_rows;
     a.n_bufs = t.n_bufs;
     // what the kernel assumes, checked before anything is launched
     if (t.p.nt != 4 || t.vec != 4) return SCONV_ERR_PLAN;
@@ -500,8 +511,10 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;
     hipStream_t s = static_cast<hipStream_t>(stream);
-#define X(TT, RW) \
-    if (t.p.t == TT && t.p.rows_w == RW) return launch_lds2_inst<TT, RW>(a, grid, threads, t.lds_bytes, s, hip_err);
+    const int step = t.p.strip ? t.p.strip : 64;
+    if (t.p.strip && (t.strip_rows < 1 || t.strip_rows * t.p.strip > 64 || t.p.band > t.p.cg * t.strip_rows)) return SCONV_ERR_PLAN;
+#define X(TT, RW, ST) \
+    if (t.p.t == TT && t.p.rows_w == RW && step == ST) return launch_lds2_inst<TT, RW, ST>(a, grid, threads, t.lds_bytes, s, hip_err);
     SCONV_LDS2_SHAPES(X)
 #undef X
     return SCONV_ERR_PLAN;

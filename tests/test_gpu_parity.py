@@ -87,6 +87,7 @@ def test_every_kernel_shape_on_a_ragged_batch(oracle, plan):
 
 
 BIG = wl.small_layer("big", C=10, H=27, W=27, K=42, R=5, S=5, stride=1, pad=2, groups=2)
+WIDE = wl.small_layer("wide", C=3, H=21, W=57, K=14, R=3, S=3, stride=1, pad=0, groups=1)
 # every accumulator shape (T, R) of the flat-stream kernel: T follows from the band height, R = rows_w
 FLAT_SHAPES = [
     (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=16, t=1, band=4)),
@@ -104,10 +105,23 @@ FLAT_SHAPES = [
     (BIG, dict(kernel=3, nt=4, cb=3, waves=16, cg=1, rows_w=3, t=7, band=14)),
     (BIG, dict(kernel=3, nt=4, cb=2, waves=16, cg=2, rows_w=3, t=7, band=27)),
     (BIG, dict(kernel=3, nt=4, cb=1, waves=16, cg=1, rows_w=1, t=13, band=27)),
+    # lanes as blocks of rows x columns (strips): 27 columns in 3 strips of 9, bands of 7 rows (the last has 6)
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9)),
+    (BIG, dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=6, t=3, band=7, strip=9)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=8, cg=1, rows_w=8, t=3, band=5, strip=9)),
+    (BIG, dict(kernel=3, nt=4, cb=2, waves=16, cg=2, rows_w=6, t=3, band=14, strip=9)),   # two waves stacked
+    (BIG, dict(kernel=3, nt=4, cb=1, waves=16, cg=4, rows_w=8, t=3, band=20, strip=9)),  # four waves stacked
+    (WIDE, dict(kernel=3, nt=4, cb=2, waves=16, cg=1, rows_w=2, t=7, band=8, strip=8)),   # 55 columns in 7 strips of 8
+    (WIDE, dict(kernel=3, nt=4, cb=1, waves=16, cg=2, rows_w=3, t=7, band=12, strip=8)),
+    (MID, dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=3, t=7, band=8, strip=8)),    # strips far wider than the image
 ]
 
 
-@pytest.mark.parametrize("case", FLAT_SHAPES, ids=[f"T{p['t']}R{p['rows_w']}cg{p['cg']}" for _, p in FLAT_SHAPES])
+def _shape_id(p):
+    return f"T{p['t']}R{p['rows_w']}cg{p['cg']}" + (f"strip{p['strip']}b{p['band']}" if p.get("strip") else "")
+
+
+@pytest.mark.parametrize("case", FLAT_SHAPES, ids=[_shape_id(p) for _, p in FLAT_SHAPES])
 def test_every_flat_stream_shape(oracle, case):
     layer, plan = case
     x, w = rand_case(layer, 9, 0.2, seed=61)
