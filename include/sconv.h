@@ -179,6 +179,24 @@ void sconv_machine_gfx950(sconv_machine *m);
 int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
                         const sconv_machine *m, sconv_prediction *out);
 
+/*
+ * How evenly the packing spreads the nonzeros (the load-balance step of the
+ * path; the paper only asks that all cores be used, Section 3).  The waves of a
+ * workgroup meet at a barrier after every channel block, so a block costs what
+ * its longest wave stream costs.  All counts are in stream chunks of 8 entries.
+ * Only for handles packed for kernel 3 (SCONV_ERR_PLAN otherwise).
+ */
+typedef struct {
+    int64_t nnz;             /* real nonzeros */
+    int64_t stream_entries;  /* entries in the streams, chunk padding included */
+    double wave_mean;        /* sum over (workgroup, block) of the mean stream length of its waves */
+    double wave_max;         /* same with the longest wave: wave_max / wave_mean >= 1 is the barrier loss */
+    double simd_max;         /* same with the longest of the 4 SIMDs (waves w, w+4, ... summed, per wave) */
+    double workgroup_mean;   /* mean over workgroups of their total of per-block longest streams */
+    double workgroup_max;    /* the largest such total: the workgroup the launch waits for */
+} sconv_balance;
+int sconv_csr_balance(const sconv_csr *h, sconv_balance *out);
+
 /* ---- the pruning controller's decision (Section 2.3, the Guided Sparsity Learning algorithm) ---- */
 
 /*

@@ -42,9 +42,14 @@ class sconv_prediction(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class sconv_balance(C.Structure):
+    _fields_ = [("nnz", C.c_int64), ("stream_entries", C.c_int64)] + \
+               [(n, C.c_double) for n in ("wave_mean", "wave_max", "simd_max", "workgroup_mean", "workgroup_max")]
+
+
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
-           "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide"]
+           "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance"]
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
@@ -79,6 +84,7 @@ def lib():
                                           C.POINTER(sconv_prediction)]
         L.sconv_gsl_decide.argtypes = [C.POINTER(sconv_desc), i32, C.c_double, i32, C.POINTER(sconv_machine),
                                        C.POINTER(i32), C.POINTER(sconv_prediction)]
+        L.sconv_csr_balance.argtypes = [C.c_void_p, C.POINTER(sconv_balance)]
         _lib = L
     return _lib
 
@@ -214,6 +220,13 @@ def sconv_model_predict(layer, N: int, density: float, csr: Csr | None = None, m
                                      C.byref(machine) if machine is not None else None, C.byref(p)),
            "sconv_model_predict")
     return p.as_dict()
+
+
+def sconv_csr_balance(h) -> dict:
+    """Load-balance figures of the kernel-3 packing (stream chunks of 8 entries)."""
+    b = sconv_balance()
+    _check(lib().sconv_csr_balance(h.handle, C.byref(b)), "sconv_csr_balance")
+    return {n: getattr(b, n) for n, _ in sconv_balance._fields_}
 
 
 def sconv_gsl_decide(layer, N: int, density: float, stabilized: bool = False, machine: sconv_machine | None = None):

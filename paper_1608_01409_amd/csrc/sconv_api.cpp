@@ -158,6 +158,48 @@ extern "C" int sconv_csr_info(const sconv_csr *h, int64_t *nnz, int32_t *out_h, 
     return SCONV_OK;
 }
 
+extern "C" int sconv_csr_balance(const sconv_csr *h, sconv_balance *out)
+{
+    if (!h || !out) return SCONV_ERR_NULL;
+    if (!h->has_lds || !h->flat) return SCONV_ERR_PLAN;
+    const PackedFlat &f = h->lds_flat;
+    const LdsTiling &t = f.t;
+    std::memset(out, 0, sizeof(*out));
+    out->nnz = (int64_t)h->canon.val.size();
+    const int n_wg = t.wave_slots / t.rg; // groups * nkt workgroups' worth of row tiles
+    double wg_sum = 0, wg_max = 0;
+    for (int wg = 0; wg < n_wg; ++wg) {
+        double wg_total = 0;
+        for (int b = 0; b < t.nblk; ++b) {
+            double sum = 0, mx = 0, simd[4] = {0, 0, 0, 0};
+            int on_simd[4] = {0, 0, 0, 0};
+            for (int r = 0; r < t.rg; ++r) {
+                const double ch = f.seg[((size_t)(wg * t.rg + r) * t.nblk + b) * 2 + 1];
+                out->stream_entries += (int64_t)ch * SCONV_FLAT_CHUNK;
+                sum += ch;
+                mx = std::max(mx, ch);
+                // the cg waves of a row group run the same stream; wave index = r * cg + column group
+                for (int c = 0; c < t.p.cg; ++c) {
+                    simd[(r * t.p.cg + c) & 3] += ch;
+                    on_simd[(r * t.p.cg + c) & 3]++;
+                }
+            }
+            double smx = 0;
+            for (int q = 0; q < 4; ++q)
+                if (on_simd[q]) smx = std::max(smx, simd[q] / on_simd[q]);
+            out->wave_mean += sum / t.rg;
+            out->wave_max += mx;
+            out->simd_max += smx;
+            wg_total += mx;
+        }
+        wg_sum += wg_total;
+        wg_max = std::max(wg_max, wg_total);
+    }
+    out->workgroup_mean = n_wg ? wg_sum / n_wg : 0;
+    out->workgroup_max = wg_max;
+    return SCONV_OK;
+}
+
 static int export_canonical(const sconv_desc &d, const Canonical &c, int32_t *rowptr, int32_t *off, float *values,
                             int64_t *nnz_io)
 {

@@ -250,3 +250,33 @@ def test_gsl_decision_matches_oracle():
     a = C.c_int32()
     assert L.sconv_gsl_decide(C.byref(d), 1, 0.0, 0, None, C.byref(a), None) == B.ERR["DESC"]
     assert L.sconv_gsl_decide(C.byref(d), 1, 0.5, 0, None, None, None) == B.ERR["NULL"]
+
+
+def test_balance_report_counts_streams_and_sees_skew():
+    """sconv_csr_balance: chunk totals are consistent with the packing, per-block dealing keeps the waves of
+    a workgroup level on a uniform mask, and a skewed mask (20 % empty rows, power-law row lengths) stays
+    close to it: the rows are dealt so that each wave's stream is level block by block."""
+    layer = wl.LAYERS["conv3"]
+    plan = dict(kernel=3, nt=4, cb=22, waves=16, cg=1, rows_w=6, t=3)
+    _, w = wl.make_case(1, 1, layer, 1, 0.10)
+    h = B.sconv_create_csr(layer, w, plan)
+    b = B.sconv_csr_balance(h)
+    assert b["nnz"] == np.count_nonzero(w)
+    assert b["nnz"] <= b["stream_entries"] < 1.06 * b["nnz"] and b["stream_entries"] % 8 == 0
+    n_wg, rg, nblk = 4, 16, 12   # 384 rows in tiles of 96; 256 channels in blocks of 22
+    assert math.isclose(b["wave_mean"] * rg * 8, b["stream_entries"], rel_tol=1e-12)
+    assert b["wave_mean"] <= b["simd_max"] <= b["wave_max"]
+    assert b["wave_max"] / b["wave_mean"] < 1.10
+    assert b["workgroup_mean"] <= b["workgroup_max"] < 1.05 * b["workgroup_mean"]
+    assert math.isclose(b["workgroup_mean"] * n_wg, b["wave_max"], rel_tol=1e-12)
+    _, ws = wl.make_case(3, 0, layer, 1, 0.10, skewed=True)
+    hs = B.sconv_create_csr(layer, ws, plan)
+    bs = B.sconv_csr_balance(hs)
+    assert bs["nnz"] == np.count_nonzero(ws)
+    assert bs["wave_max"] / bs["wave_mean"] < 1.25
+    assert bs["workgroup_max"] / bs["workgroup_mean"] < 1.10
+    # a handle without a kernel-3 packing has nothing to report
+    hd = B.sconv_create_csr(layer, w, dict(kernel=2))
+    out = B.sconv_balance()
+    assert B.lib().sconv_csr_balance(hd.handle, C.byref(out)) == B.ERR["PLAN"]
+    assert B.lib().sconv_csr_balance(h.handle, None) == B.ERR["NULL"]
