@@ -292,12 +292,15 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     const unsigned ldsbase = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void *)smem4;
     // cell of the plane this lane's chunk 0 sits on; chunk t is STEP cells further.  Flat: position p is
     // cell p.  Strips: lane = row * strip + column of a block of strip_rows x strip cells, the waves of a
-    // column group stacked vertically; lanes outside the block or the band read cell 0 and store nothing.
+    // column group stacked vertically; lanes outside the block or the band store nothing and read a cell of
+    // the first row that falls on the same LDS banks as their own would (cell 0 for all of them costs every
+    // read of the wave a bank conflict with the lane that owns that bank).
     int cell0 = cgi * T * 64 + lane;
     if (STEP != 64) {
         const int by = lane / a.strip, bx = lane - by * a.strip;
         const int y = cgi * a.strip_rows + by;
-        cell0 = (by < a.strip_rows && y < a.band) ? y * a.Wl + bx : 0;
+        cell0 = y * a.Wl + bx;
+        if (by >= a.strip_rows || y >= a.band) cell0 &= 15;
     }
     Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc, a.seg + (size_t)wslot * a.nblk * 2,
                        a.row_of + (size_t)wslot * R,
