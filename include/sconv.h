@@ -63,10 +63,15 @@ typedef struct {
  * span 64 consecutive cells of the padded plane, chunk after chunk; w > 0 =
  * they span a block of 64/w output rows by w output columns and the t chunks of
  * a wave are t such blocks side by side (t*w >= OW, band <= cg * (64/w)),
- * which wastes fewer lanes when OW is a little under t*w.
+ * which wastes fewer lanes when OW is a little under t*w.  `splits` (kernel 3
+ * only; 0 or 1 = none): that many workgroups share the channel blocks of a
+ * tile and add their partial sums to the zeroed output with floating-point
+ * atomics, for launches that would otherwise leave compute units idle; the
+ * order of those additions, and so the last bits of the result, can differ
+ * from run to run.
  */
 typedef struct {
-    int32_t kernel, nt, cb, waves, cg, rows_w, t, band, strip;
+    int32_t kernel, nt, cb, waves, cg, rows_w, t, band, strip, splits;
 } sconv_plan;
 
 typedef struct sconv_csr sconv_csr; /* opaque, owned by the library */
@@ -119,6 +124,19 @@ int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t
  * waited for.  `in` and `out` must not overlap.
  */
 int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream);
+
+/*
+ * The same with a bias and a ReLU applied before the result is stored: out =
+ * max(conv + bias[k], 0).  Not part of the paper's method: the networks it
+ * evaluates (Section 3) apply both after every convolution, and fusing them
+ * saves a pass over the output.  `bias` [device] holds K
+ * floats or is NULL (none); relu != 0 clamps at zero.  The flat-stream kernel
+ * applies both to its accumulators; the other kernels, and launches that split
+ * the channels over workgroups, run an elementwise pass of their own after the
+ * convolution.
+ */
+int sconv_forward_fused(sconv_csr *h, const float *in, float *out, int32_t N, const float *bias, int32_t relu,
+                        void *hip_stream);
 
 /* The last HIP error code seen by a call on this handle (0 if none). */
 int sconv_last_hip_error(const sconv_csr *h);

@@ -124,3 +124,19 @@ def sparse_conv(layer, w: np.ndarray, x: np.ndarray):
     off = lower_offsets(layer, rowptr, colidx)
     out, ab = forward_f64(layer, rowptr, off, val, x)
     return out, ab, (rowptr, colidx, off, val)
+
+
+def bias_relu(out: np.ndarray, absum: np.ndarray, bias, relu: bool):
+    """Epilogue applied to a convolution result [N][K][OH][OW] in fp64: out + bias[k], then max(., 0).
+    (Not in the paper; the plain definition of the bias and ReLU layers that follow a convolution.)
+    Returns (result, scale): scale = absum + |bias[k]| is the sum of the magnitudes of everything added
+    into an output, the yardstick of the fp32 tolerance."""
+    res = np.array(out, dtype=np.float64, copy=True)
+    scale = np.array(absum, dtype=np.float64, copy=True)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64).reshape(1, -1, 1, 1)
+        res += b
+        scale += np.abs(b)
+    if relu:
+        res = np.where(res > 0, res, 0.0)
+    return res, scale

@@ -21,7 +21,7 @@ class sconv_desc(C.Structure):
 
 
 class sconv_plan(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("kernel", "nt", "cb", "waves", "cg", "rows_w", "t", "band", "strip")]
+    _fields_ = [(n, C.c_int32) for n in ("kernel", "nt", "cb", "waves", "cg", "rows_w", "t", "band", "strip", "splits")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -48,7 +48,7 @@ class sconv_balance(C.Structure):
 
 
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
-           "sconv_csr_unpack", "sconv_forward", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
+           "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
            "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance"]
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
@@ -73,6 +73,7 @@ def lib():
         L.sconv_csr_export.argtypes = [vp, vp, vp, vp, i64p]
         L.sconv_csr_unpack.argtypes = [vp, i32, vp, vp, vp, i64p]
         L.sconv_forward.argtypes = [vp, vp, vp, i32, vp]
+        L.sconv_forward_fused.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_last_hip_error.argtypes = [vp]
         L.sconv_destroy_csr.argtypes = [vp]
         L.sconv_destroy_csr.restype = None
@@ -204,6 +205,32 @@ def sconv_forward(csr: Csr, x, out=None, stream=None):
                                  C.c_void_p(s.cuda_stream))
     if rc != SCONV_OK:
         raise SconvError(rc, f"sconv_forward (hip error {lib().sconv_last_hip_error(csr.handle)})")
+    return out
+
+
+def sconv_forward_fused(csr: Csr, x, bias=None, relu=False, out=None, stream=None):
+    """sconv_forward followed, inside the kernel where it can, by out = max(out + bias[k], 0); bias: fp32 CUDA
+    tensor [K] or None."""
+    import torch
+
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    L = csr.layer
+    assert tuple(x.shape[1:]) == (L.C, L.H, L.W), (tuple(x.shape), L)
+    N = x.shape[0]
+    info = sconv_csr_info(csr)
+    if out is None:
+        out = torch.empty((N, L.K, info["OH"], info["OW"]), dtype=torch.float32, device=x.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+    assert tuple(out.shape) == (N, L.K, info["OH"], info["OW"])
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and tuple(bias.shape) == (L.K,)
+    s = stream if stream is not None else torch.cuda.current_stream(x.device)
+    with torch.cuda.device(x.device):
+        rc = lib().sconv_forward_fused(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N,
+                                       C.c_void_p(bias.data_ptr()) if bias is not None else None, int(bool(relu)),
+                                       C.c_void_p(s.cuda_stream))
+    if rc != SCONV_OK:
+        raise SconvError(rc, f"sconv_forward_fused (hip error {lib().sconv_last_hip_error(csr.handle)})")
     return out
 
 

@@ -58,7 +58,8 @@ MAX_VGPR = 128
 OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
 
 OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase", "slab0", "slabstep", "nslab",
-       "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff"]
+       "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff", "outp_hi", "nch", "nblk", "bias", "flags"]
+FLAG_RELU, FLAG_ATOMIC = 0, 1   # bits of the flags operand
 OP = {n: f"%{i}" for i, n in enumerate(OPS)}
 
 
@@ -159,8 +160,8 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_load_dwordx8 s[{SN}:{SN + 7}], {OP['kern']}, {hex(OFF_CONSTS)}")
     emit("s_waitcnt lgkmcnt(0)")
     emit(f"s_mov_b32 s{SCB}, s{SN}")
-    emit(f"s_mov_b32 s{SNBLK}, s{SN + 1}")
-    emit(f"s_mov_b32 s{SREM}, s{SN + 2}")
+    emit(f"s_mov_b32 s{SNBLK}, {OP['nblk']}")      # blocks and channels of this workgroup's channel range
+    emit(f"s_mov_b32 s{SREM}, {OP['nch']}")
     emit(f"s_mov_b32 s{SPLANE}, s{SN + 3}")
     emit(f"s_mov_b32 s{SSTRIDE}, s{SN + 4}")
     emit(f"s_mov_b32 s{SHW4}, s{SN + 5}")
@@ -239,47 +240,76 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_cmp_lt_u32 s{SBLK}, s{SNBLK}")
     emit(f"s_cbranch_scc1 {blk}")
 
-    # ------------------------------------------------------------------ stores
+    # ------------------------------------------------------------------ epilogue and stores
     KROW = SA                    # k of row i in s[KROW + i], R <= 16
-    BASE = SB                    # 64-bit output base of row i in s[BASE + 2i : +1]
+    BASE = SB                    # 64-bit output base of row i in s[BASE + 2i : +1]; before that, the row's bias
     emit(f"s_load_dwordx2 s[{SX0}:{SX1}], {OP['kern']}, {hex(OFF_TBL)}")
-    emit(f"s_load_dwordx2 s[{SPTR}:{SPTR + 1}], {OP['kern']}, {hex(OFF_CONSTS + 24)}")   # OHW4, img_stride
+    emit(f"s_load_dwordx2 s[{SPTR}:{SPTR + 1}], {OP['kern']}, {hex(OFF_CONSTS + 24)}")   # row stride, image stride of out
     for i in range(R):
         emit(f"s_load_dword s{KROW + i}, {OP['rowp']}, {hex(4 * i)}")
     emit("s_waitcnt lgkmcnt(0)")
     for t in range(T):
         emit(f"global_load_dword v{RING0 + t}, {OP['tbloff']}, s[{SX0}:{SX1}] offset:{t * 256}")
+    # bias (a null pointer = none) and ReLU on the accumulators, before anything is stored
+    nobias, norelu = label("nobias"), label("norelu")
+    emit(f"s_cmp_eq_u64 {OP['bias']}, 0")
+    emit(f"s_cbranch_scc1 {nobias}")
+    for i in range(R):
+        emit(f"s_max_i32 s{STMP}, s{KROW + i}, 0")          # rows that do not exist (-1) read bias[0], unused
+        emit(f"s_lshl_b32 s{STMP}, s{STMP}, 2")
+        emit(f"s_load_dword s{BASE + i}, {OP['bias']}, s{STMP}")
+    emit("s_waitcnt lgkmcnt(0)")
+    for i in range(R):
+        for n in range(T * 4):
+            emit(f"v_add_f32 v{ACC0 + i * T * 4 + n}, s{BASE + i}, v{ACC0 + i * T * 4 + n}")
+    emit(f"{nobias}:")
+    emit(f"s_bitcmp1_b32 {OP['flags']}, {FLAG_RELU}")
+    emit(f"s_cbranch_scc0 {norelu}")
+    for n in range(nacc):
+        emit(f"v_max_f32 v{ACC0 + n}, 0, v{ACC0 + n}")
+    emit(f"{norelu}:")
     for i in range(R):
         emit(f"s_mul_hi_u32 s{STMP}, s{KROW + i}, s{SPTR}")
         emit(f"s_mul_i32 s{SCNT}, s{KROW + i}, s{SPTR}")
-        emit(f"s_add_u32 s{BASE + 2 * i}, {OP['outp']}_LO, s{SCNT}")
-        emit(f"s_addc_u32 s{BASE + 2 * i + 1}, {OP['outp']}_HI, s{STMP}")
+        emit(f"s_add_u32 s{BASE + 2 * i}, {OP['outp']}, s{SCNT}")
+        emit(f"s_addc_u32 s{BASE + 2 * i + 1}, {OP['outp_hi']}, s{STMP}")
     emit("s_waitcnt vmcnt(0)")
-    for t in range(T):
-        emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")   # the compare writes vcc for active lanes only
-        emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
-        emit("s_mov_b64 exec, vcc")
-        for i in range(R):
-            rowend = label("rowend")
-            emit(f"s_cmp_lt_i32 s{KROW + i}, 0")
-            emit(f"s_cbranch_scc1 {rowend}")
-            emit(f"s_mov_b64 s[{SX0}:{SX1}], s[{BASE + 2 * i}:{BASE + 2 * i + 1}]")
-            for e in range(4):
-                if e:
-                    emit(f"s_cmp_le_u32 {OP['nimg']}, {e}")
-                    emit(f"s_cbranch_scc1 {rowend}")
-                    emit(f"s_add_u32 s{SX0}, s{SX0}, s{SPTR + 1}")
-                    emit(f"s_addc_u32 s{SX1}, s{SX1}, 0")
-                emit(f"global_store_dword v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
-            emit(f"{rowend}:")
+
+    def store_all(instr):
+        for t in range(T):
+            emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")   # the compare writes vcc for active lanes only
+            emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
+            emit("s_mov_b64 exec, vcc")
+            for i in range(R):
+                rowend = label("rowend")
+                emit(f"s_cmp_lt_i32 s{KROW + i}, 0")
+                emit(f"s_cbranch_scc1 {rowend}")
+                emit(f"s_mov_b64 s[{SX0}:{SX1}], s[{BASE + 2 * i}:{BASE + 2 * i + 1}]")
+                for e in range(4):
+                    if e:
+                        emit(f"s_cmp_le_u32 {OP['nimg']}, {e}")
+                        emit(f"s_cbranch_scc1 {rowend}")
+                        emit(f"s_add_u32 s{SX0}, s{SX0}, s{SPTR + 1}")
+                        emit(f"s_addc_u32 s{SX1}, s{SX1}, 0")
+                    emit(f"{instr} v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
+                emit(f"{rowend}:")
+
+    # a workgroup that holds only part of the input channels adds its partial sums to a zeroed output
+    plain, done = label("plain"), label("stored")
+    emit(f"s_bitcmp1_b32 {OP['flags']}, {FLAG_ATOMIC}")
+    emit(f"s_cbranch_scc0 {plain}")
+    store_all("global_atomic_add_f32")
+    emit(f"s_branch {done}")
+    emit(f"{plain}:")
+    store_all("global_store_dword")
+    emit(f"{done}:")
     emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
 
     ins = ('"s"(kern), "s"(rsrc), "s"(segp), "s"(rowp), "s"(outp_lo), "s"(soff0), "s"(nimg), "s"(lim), "s"(ldsbase), '
            '"s"(slab0), "s"(slabstep), "s"(nslab), "v"(lane_byte), "v"(voff0), "v"(voff1), "v"(voff2), "v"(voff3), '
-           '"v"(tbloff), "s"(outp_hi)')
+           '"v"(tbloff), "s"(outp_hi), "s"(nch), "s"(nblk), "s"(bias), "s"(flags)')
     text = []
     for ins_ in L:
-        ins_ = ins_.replace(f"{OP['outp']}_LO", OP['outp']).replace(f"{OP['outp']}_HI", f"%{len(OPS)}")
         text.append(f'            "{ins_}\\n\\t"')
     clob = [f'"v{r}"' for r in range(ACC0, MAX_VGPR)]
     clob += [f'"s{r}"' for r in list(range(28, 32)) + list(range(34, 100))]
@@ -292,7 +322,8 @@ struct Lds2Asm<{T}, {R}, {step}> {{
                                                unsigned outp_lo, unsigned outp_hi, unsigned soff0, unsigned nimg,
                                                unsigned lim, unsigned ldsbase, unsigned slab0, unsigned slabstep,
                                                unsigned nslab, unsigned lane_byte, unsigned voff0, unsigned voff1,
-                                               unsigned voff2, unsigned voff3, unsigned tbloff)
+                                               unsigned voff2, unsigned voff3, unsigned tbloff, unsigned nch, unsigned nblk,
+                                               unsigned long long bias, unsigned flags)
     {{
         asm volatile(
 {chr(10).join(text)}

@@ -250,14 +250,32 @@ extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowp
     return export_canonical(h->desc, c, rowptr, off, values, nnz_io);
 }
 
+static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream);
+
 extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream)
+{
+    return forward_impl(h, in, out, N, Epilogue(), hip_stream);
+}
+
+extern "C" int sconv_forward_fused(sconv_csr *h, const float *in, float *out, int32_t N, const float *bias, int32_t relu,
+                                   void *hip_stream)
+{
+    Epilogue ep;
+    ep.bias = bias;
+    ep.relu = relu != 0;
+    return forward_impl(h, in, out, N, ep, hip_stream);
+}
+
+static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream)
 {
     if (!h || !in || !out) return SCONV_ERR_NULL;
     if (N < 1) return SCONV_ERR_BATCH;
+    const Geometry og = geometry(h->desc);
+    const int64_t out_rows = (int64_t)N * h->desc.K, out_inner = (int64_t)og.OH * og.OW;
     bool use_lds = h->has_lds;
     // a tiling the library chose itself follows the batch size (only when none of its fields was requested)
     const sconv_plan &rq = h->requested;
-    const bool free_choice = !rq.nt && !rq.cb && !rq.waves && !rq.cg && !rq.rows_w && !rq.t && !rq.band;
+    const bool free_choice = !rq.nt && !rq.cb && !rq.waves && !rq.cg && !rq.rows_w && !rq.t && !rq.band && !rq.strip && !rq.splits;
     if (use_lds && free_choice && N >= 4 && N != h->planned_n) {
         try {
             const int prc = plan_lds(h, N);
@@ -294,7 +312,17 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
             if (rc) return rc;
             h->lds_uploaded = true;
         }
-        return launch_lds2(h->kdesc, f_tiling(h), h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+        const LdsTiling &ft = f_tiling(h);
+        const bool split = ft.p.splits > 1;
+        if (split) { // partial sums are added to a zeroed output
+            rc = launch_fill_zero(out, out_rows * out_inner, hip_stream, &h->hip_err);
+            if (rc) return rc;
+        }
+        rc = launch_lds2(h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, ep, hip_stream, &h->hip_err);
+        if (rc || !split || !ep.relu) return rc;
+        Epilogue clamp;
+        clamp.relu = true;
+        return launch_epilogue(out, out_rows, out_inner, h->desc.K, clamp, hip_stream, &h->hip_err);
     }
     if (use_lds) {
         if (!h->lds_uploaded) {
@@ -304,7 +332,8 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
             if (rc) return rc;
             h->lds_uploaded = true;
         }
-        return launch_lds(h->kdesc, h->lds.t, h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+        rc = launch_lds(h->kdesc, h->lds.t, h->dev_lds, in, out, N, hip_stream, &h->hip_err);
+        return rc ? rc : launch_epilogue(out, out_rows, out_inner, h->desc.K, ep, hip_stream, &h->hip_err);
     }
     if (!h->direct_uploaded) {
         rc = upload(h->direct.rowptr.data(), h->direct.rowptr.size() * 4, &h->dev_direct.rowptr, &h->hip_err);
@@ -312,7 +341,8 @@ extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t 
         if (rc) return rc;
         h->direct_uploaded = true;
     }
-    return launch_direct(h->desc, h->dev_direct, in, out, N, hip_stream, &h->hip_err);
+    rc = launch_direct(h->desc, h->dev_direct, in, out, N, hip_stream, &h->hip_err);
+    return rc ? rc : launch_epilogue(out, out_rows, out_inner, h->desc.K, ep, hip_stream, &h->hip_err);
 }
 
 extern "C" int sconv_last_hip_error(const sconv_csr *h) { return h ? h->hip_err : 0; }

@@ -121,6 +121,9 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
         return SCONV_ERR_PLAN;
     }
     t.strip_rows = p.strip ? 64 / p.strip : 0;
+    t.out_pos = 1;
+    if (p.splits < 0 || (p.splits > 1 && t.p.kernel != 3)) return SCONV_ERR_PLAN;
+    if (t.p.splits == 0) t.p.splits = 1;
     if (t.p.band == 0) t.p.band = p.strip ? std::min(g.OH, p.cg * t.strip_rows) : g.OH;
     t.n_bands = ceil_div(g.OH, t.p.band);
     t.Wl = lds_pitch(d, p.strip);
@@ -138,6 +141,9 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     }
     if (p.cb > g.Cg) t.p.cb = g.Cg;
     t.nblk = ceil_div(g.Cg, t.p.cb);
+    if (t.p.splits > t.nblk) return SCONV_ERR_PLAN;
+    // every part takes ceil(nblk / splits) blocks; fewer parts if the last ones would be empty
+    t.p.splits = ceil_div(t.nblk, ceil_div(t.nblk, t.p.splits));
     t.rg = p.waves / p.cg;
     const int kt = t.rg * p.rows_w;
     t.nkt = ceil_div(g.Kg, kt);
@@ -291,7 +297,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                     if (cb < 1) continue;
                     // even out the blocks
                     if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
-                    sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip};
+                    sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip, req.splits};
                     LdsTiling t;
                     if (fill_tiling(d, p, t) != SCONV_OK) continue;
                     const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
@@ -522,7 +528,7 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
             by = br < t.strip_rows ? cgi * t.strip_rows + br : t.p.band;
             ox = ch * t.p.strip + lane % t.p.strip;
         }
-        if (by < t.p.band && ox < g.OW) out.store_tbl[pos] = (by * g.OW + ox) * 4;
+        if (by < t.p.band && ox < g.OW) out.store_tbl[pos] = (by * g.OW + ox) * 4 * t.out_pos;
     }
     return SCONV_OK;
 }

@@ -62,6 +62,7 @@ struct LdsTiling {
     unsigned zero_page; // byte offset, relative to a buffer, of its all-zero page (padding entries)
     int page_cells;     // size of that page in cells of nt floats
     int strip_rows;     // strip layout: rows of the block of positions one chunk covers (64 / strip), else 0
+    int out_pos;        // floats from one output position to the next in the caller's layout (1 for NCHW)
 };
 
 struct PackedLds {
@@ -135,8 +136,26 @@ struct DeviceDirect {
 };
 int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
                int N, void *stream, int *hip_err);
-int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
-                int N, void *stream, int *hip_err);
+// Bias and ReLU applied to the outputs (bias null = none).
+struct Epilogue {
+    const float *bias = nullptr;
+    bool relu = false;
+};
+// Where the flat-stream kernel finds its operands, in floats.  Input element (image i of tile m, channel c,
+// position p = Y*W + X of the unpadded image): m*in_tile + i*in_img + c*in_ch + p*in_pos.  Output (image i
+// of tile m, row k, band b, position q inside the band): m*out_tile + b*out_band + k*out_row + i*out_img +
+// q*out_pos.  nchw_layout() gives the convolution's [N][C][H][W] -> [N][K][OH][OW].
+struct Lds2Layout {
+    int64_t in_tile, in_img, in_ch, in_pos;
+    int64_t in_rec_fixed, in_rec_img; // bytes a tile with n valid images may read: in_rec_fixed + n * in_rec_img
+    int64_t out_tile, out_band, out_row, out_img, out_pos;
+};
+Lds2Layout nchw_layout(const sconv_desc &d, const LdsTiling &t);
+int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay, const float *in,
+                float *out, int N, const Epilogue &ep, void *stream, int *hip_err);
+// out[n][k][..] = max(out + bias[k], 0) in place, for the paths that do not fuse it: rows of `inner` floats
+int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilogue &ep, void *stream, int *hip_err);
+int launch_fill_zero(float *out, int64_t n, void *stream, int *hip_err);
 // in [N][C][H][W] -> q [N][C*s*s][Hq][Wq], zero padding written out
 int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, float *q, int N, void *stream, int *hip_err);
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,

@@ -210,6 +210,17 @@ struct Lds2Args {
     int rg, cg, nkt, band, n_bands, Wl, plane_floats, n_slabs;
     int n_tiles, units, block_bytes, page_bytes, n_bufs;
     int strip, strip_rows;   // lanes of a wave span strip_rows x strip cells of the plane (0: 64 consecutive cells)
+    // input addressing in floats: element (image i of the tile, channel c, row Y, column X of the unpadded
+    // image) sits at tile * in_tile + i * in_img + c * (HW4 / 4) + (Y * W + X) * in_pos
+    long long in_tile;
+    int in_img, in_pos;
+    long long in_rec_fixed, in_rec_img; // a tile with n valid images may read in_rec_fixed + n * in_rec_img bytes; past that, 0
+    long long out_tile;      // floats from one tile's outputs to the next
+    int out_band;            // floats from one band's outputs to the next (band * OW for NCHW)
+    int out_pos4;            // bytes from one output position to the next (4 for NCHW); the store table holds multiples
+    int splits, blk_split;   // workgroups along the input channels, channel blocks each of them takes
+    const float *bias;       // [K] added to every output of row k, or null
+    int relu;                // outputs below zero become zero
 };
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -238,14 +249,18 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     const int unit = slot % a.units;
     const int tile = (slot / a.units) * 8 + xcd;
     if (tile >= a.n_tiles) return;
-    const int gk = unit / a.n_bands, band_i = unit - gk * a.n_bands;
+    const int us = unit / a.splits, split = unit - us * a.splits;
+    const int gk = us / a.n_bands, band_i = us - gk * a.n_bands;
     const int g = gk / a.nkt, kt = gk - g * a.nkt;
     const int n0 = tile * 4;
     const int y0 = band_i * a.band;
+    const int blk0 = split * a.blk_split;                                 // first channel block of this workgroup
+    const int nblk_here = min(a.blk_split, a.nblk - blk0);
+    if (nblk_here <= 0) return; // the host never launches an empty part; the block loop needs one block at least
+    const int ch0 = blk0 * a.cb, nch_here = min(nblk_here * a.cb, a.Cg - ch0);
     const int rgi = __builtin_amdgcn_readfirstlane(wave / a.cg);
     const int cgi = wave - rgi * a.cg;
     const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
-    const int HW = a.H * a.W, CHW = a.C * HW;
     const int nimg = min(4, a.N - n0);
 
     // per-lane source offsets of the slabs this wave stages, relative to channel 0 of image n0
@@ -257,7 +272,9 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         const int Y = cell / a.Wl, X = cell - Y * a.Wl;
         const int iy = y0 + Y - a.pad, ix = X - a.pad;
         const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-        voff[j] = f >= a.plane_floats ? kSkipLane : inside ? (unsigned)(img * CHW + iy * a.W + ix) * 4u : kZeroLane;
+        voff[j] = f >= a.plane_floats ? kSkipLane
+                  : inside            ? (unsigned)(img * a.in_img + (iy * a.W + ix) * a.in_pos) * 4u
+                                      : kZeroLane;
     }
     int nslab = 0;
 #pragma unroll
@@ -280,15 +297,15 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         }
     }
 
-    const float *in_tile = a.in + (size_t)n0 * CHW;
+    const float *in_tile = a.in + (size_t)tile * a.in_tile;
     const unsigned long long ip = (unsigned long long)in_tile;
     int4v rsrc;
     rsrc.x = __builtin_amdgcn_readfirstlane((int)(unsigned)ip);
     rsrc.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(ip >> 32));   // stride 0
-    rsrc.z = __builtin_amdgcn_readfirstlane(nimg * CHW * 4);              // bytes past which loads return 0
+    rsrc.z = __builtin_amdgcn_readfirstlane((int)(a.in_rec_fixed + a.in_rec_img * nimg)); // bytes past which loads return 0
     rsrc.w = 0x00020000;                                                   // raw 32-bit data format
-    const unsigned long long op = (unsigned long long)(a.out + ((size_t)n0 * a.K * a.OH + y0) * a.OW);
-    const unsigned lim = (unsigned)(min(a.band, a.OH - y0) * a.OW * 4);
+    const unsigned long long op = (unsigned long long)(a.out + (size_t)tile * a.out_tile + (size_t)band_i * a.out_band);
+    const unsigned lim = (unsigned)(min(a.band, a.OH - y0) * a.OW * a.out_pos4);
     const unsigned ldsbase = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void *)smem4;
     // cell of the plane this lane's chunk 0 sits on; chunk t is STEP cells further.  Flat: position p is
     // cell p.  Strips: lane = row * strip + column of a block of strip_rows x strip cells, the waves of a
@@ -302,13 +319,22 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         cell0 = y * a.Wl + bx;
         if (by >= a.strip_rows || y >= a.band) cell0 &= 15;
     }
-    Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc, a.seg + (size_t)wslot * a.nblk * 2,
+    // the first split adds the bias
+    const unsigned long long bias_all = (unsigned long long)a.bias;
+    const unsigned bias_lo = (unsigned)__builtin_amdgcn_readfirstlane(split == 0 ? (int)(unsigned)bias_all : 0);
+    const unsigned bias_hi = (unsigned)__builtin_amdgcn_readfirstlane(split == 0 ? (int)(unsigned)(bias_all >> 32) : 0);
+    const unsigned long long bias = ((unsigned long long)bias_hi << 32) | bias_lo;
+    const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane((a.relu ? 1 : 0) | (a.splits > 1 ? 2 : 0));
+    Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
+                       a.seg + ((size_t)wslot * a.nblk + blk0) * 2,
                        a.row_of + (size_t)wslot * R,
                        __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
-                       (unsigned)__builtin_amdgcn_readfirstlane(g * a.Cg * HW * 4), (unsigned)nimg, lim,
+                       (unsigned)__builtin_amdgcn_readfirstlane((g * a.Cg + ch0) * a.HW4), (unsigned)nimg, lim,
                        __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)(wave * 256), (unsigned)(n_waves * 256),
                        (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)(cell0 * 16), voff[0],
-                       voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4));
+                       voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4),
+                       (unsigned)__builtin_amdgcn_readfirstlane(nch_here), (unsigned)__builtin_amdgcn_readfirstlane(nblk_here),
+                       bias, flags);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -478,8 +504,68 @@ int lds2_depth(int t, int rows_w)
     return 0;
 }
 
-int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const float *in, float *out,
-                int N, void *stream, int *hip_err)
+// Elementwise passes around the kernels that cannot fuse them.
+__global__ void __launch_bounds__(256) sconv_epilogue_kernel(float *out, const float *bias, int relu, long long inner, int K, long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    float v = out[i];
+    if (bias) v += bias[(int)((i / inner) % K)];
+    if (relu) v = fmaxf(v, 0.f);
+    out[i] = v;
+}
+
+__global__ void __launch_bounds__(256) sconv_fill_zero_kernel(float4 *out4, float *tail, long long n4, int n_tail)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) out4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n_tail) tail[i] = 0.f;
+}
+
+int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilogue &ep, void *stream, int *hip_err)
+{
+    if (!ep.bias && !ep.relu) return SCONV_OK;
+    const int64_t total = rows * inner, gx = (total + 255) / 256;
+    if (gx > 0x7fffffff) return SCONV_ERR_RANGE;
+    hipLaunchKernelGGL(sconv_epilogue_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream), out, ep.bias,
+                       ep.relu ? 1 : 0, (long long)inner, K, (long long)total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+// A fill kernel rather than a memset node: safe to record into a graph the caller captures.
+int launch_fill_zero(float *out, int64_t n, void *stream, int *hip_err)
+{
+    if (((uintptr_t)out & 15) != 0) return SCONV_ERR_PLAN; // device allocations are 256-byte aligned
+    const int64_t n4 = n / 4, gx = (std::max<int64_t>(n4, 1) + 255) / 256;
+    if (gx > 0x7fffffff) return SCONV_ERR_RANGE;
+    hipLaunchKernelGGL(sconv_fill_zero_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<float4 *>(out), out + n4 * 4, (long long)n4, (int)(n - n4 * 4));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+Lds2Layout nchw_layout(const sconv_desc &d, const LdsTiling &t)
+{
+    const Geometry g = geometry(d);
+    Lds2Layout l;
+    const int64_t HW = (int64_t)d.H * d.W, OHW = (int64_t)g.OH * g.OW;
+    l.in_img = d.C * HW; l.in_tile = 4 * l.in_img; l.in_ch = HW; l.in_pos = 1;
+    l.in_rec_fixed = 0; l.in_rec_img = l.in_img * 4;
+    l.out_img = d.K * OHW; l.out_tile = 4 * l.out_img; l.out_band = (int64_t)t.p.band * g.OW; l.out_row = OHW; l.out_pos = 1;
+    return l;
+}
+
+int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay, const float *in,
+                float *out, int N, const Epilogue &ep, void *stream, int *hip_err)
 {
     const Geometry g = geometry(d);
     Lds2Args a;
@@ -491,25 +577,39 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     a.store_tbl = static_cast<const int *>(dev.store_tbl);
     const int plane_floats = t.plane_cells * 4;
     a.cb = t.p.cb; a.nblk = t.nblk; a.Cg = g.Cg; a.plane_bytes = plane_floats * 4;
-    a.buf_stride_bytes = t.buf_stride_floats * 4; a.HW4 = d.H * d.W * 4; a.OHW4 = g.OH * g.OW * 4;
+    a.buf_stride_bytes = t.buf_stride_floats * 4;
     a.N = N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.OH = g.OH; a.OW = g.OW; a.pad = d.pad;
     a.rg = t.rg; a.cg = t.p.cg; a.nkt = t.nkt; a.band = t.p.band; a.n_bands = t.n_bands; a.Wl = t.Wl;
     a.plane_floats = plane_floats; a.n_slabs = t.n_slabs;
     a.n_tiles = (N + 3) / 4;
-    a.units = d.groups * t.nkt * t.n_bands;
+    a.splits = std::max(1, t.p.splits);
+    a.blk_split = (t.nblk + a.splits - 1) / a.splits;
+    if ((a.splits - 1) * a.blk_split >= t.nblk) return SCONV_ERR_PLAN; // a part without blocks
+    a.units = d.groups * t.nkt * t.n_bands * a.splits;
     a.block_bytes = (int)t.zero_page;
     a.page_bytes = t.page_cells * 16;
     a.strip = t.p.strip; a.strip_rows = t.strip_rows;
     a.n_bufs = t.n_bufs;
+    a.bias = ep.bias;
+    a.relu = (ep.relu && a.splits == 1) ? 1 : 0;   // partial sums cannot be clamped: a pass of its own follows
+    // offsets the kernel keeps in 32 bits
+    const int64_t lim32 = (int64_t)1 << 31;
+    if (lay.in_img * 4 * 4 >= lim32 || lay.in_ch * 4 >= lim32 || lay.in_pos * 4 * d.H * d.W >= lim32) return SCONV_ERR_RANGE;
+    if ((int64_t)d.C * lay.in_ch * 4 + 3 * lay.in_img * 4 >= lim32) return SCONV_ERR_RANGE;   // buffer offsets below 2^31 bytes
+    if (lay.out_row * 4 >= lim32 || lay.out_img * 4 >= lim32 || lay.out_band >= lim32) return SCONV_ERR_RANGE;
+    if ((int64_t)t.p.band * g.OW * lay.out_pos * 4 >= lim32) return SCONV_ERR_RANGE;
+    a.in_tile = lay.in_tile; a.in_img = (int)lay.in_img; a.in_pos = (int)lay.in_pos; a.HW4 = (int)(lay.in_ch * 4);
+    if (lay.in_rec_fixed + 4 * lay.in_rec_img >= lim32) return SCONV_ERR_RANGE;
+    a.in_rec_fixed = lay.in_rec_fixed; a.in_rec_img = lay.in_rec_img;
+    a.out_tile = lay.out_tile; a.out_band = (int)lay.out_band; a.OHW4 = (int)(lay.out_row * 4);
+    a.out_pos4 = (int)(lay.out_pos * 4);
     // what the kernel assumes, checked before anything is launched
     if (t.p.nt != 4 || t.vec != 4) return SCONV_ERR_PLAN;
     if ((t.n_slabs + t.p.waves - 1) / t.p.waves > 4) return SCONV_ERR_PLAN;
-    if ((int64_t)4 * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;   // buffer offsets below 2^31 bytes
-    if ((int64_t)d.K * g.OH * g.OW * 4 >= ((int64_t)1 << 31)) return SCONV_ERR_RANGE; // image stride of the output
     if (t.lds_bytes % 16 || t.lds_bytes > 160 * 1024 || a.block_bytes % 16 || a.buf_stride_bytes % 16) return SCONV_ERR_PLAN;
     if (a.block_bytes + a.page_bytes > a.buf_stride_bytes) return SCONV_ERR_PLAN;
     if (t.p.rows_w * t.p.t * 4 > 256) return SCONV_ERR_PLAN;
-    a.img_stride_bytes = (int)((int64_t)d.K * g.OH * g.OW * 4);
+    a.img_stride_bytes = (int)(lay.out_img * 4);
     const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;

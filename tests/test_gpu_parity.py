@@ -308,3 +308,57 @@ def test_density_sweep_ends_on_conv5(oracle, dens):
     layer = wl.LAYERS["conv5"]
     x, w = wl.make_case(2, 3, layer, 32, dens)
     check(layer, w, x, oracle, None, images=[0, 17, 31], what=f"sweep-{dens}")
+
+
+def check_fused(layer, w, x, oracle, plan, bias, relu, what=""):
+    say(f"{what} layer={layer} N={x.shape[0]} plan={plan} bias={bias is not None} relu={relu}")
+    h = B.sconv_create_csr(layer, w, plan)
+    info = B.sconv_csr_info(h)
+    xd = torch.from_numpy(x).cuda()
+    bd = torch.from_numpy(bias).cuda() if bias is not None else None
+    out = torch.full((x.shape[0], layer.K, info["OH"], info["OW"]), float("nan"), device="cuda")
+    B.sconv_forward_fused(h, xd, bd, relu, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref, ab, _ = oracle.sparse_conv(layer, w, x)
+    ref, scale = oracle.bias_relu(ref, ab, bias, relu)
+    err = np.abs(got - ref)
+    bad = err > TOL * scale
+    assert not bad.any(), (what, info["plan"], int(bad.sum()), float(err.max()), np.argwhere(bad)[:5])
+    if relu:
+        assert (got >= 0).all()
+    return info
+
+
+EPILOGUE_PLANS = [
+    None,
+    dict(kernel=2),                                                      # direct kernel: a pass of its own
+    dict(kernel=1, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),            # per-row streams: a pass of its own
+    dict(kernel=3, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),            # fused
+    dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=16, t=1, band=4),   # 16 rows per wave
+    dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=12, t=2, band=9),
+    dict(kernel=3, nt=4, cb=4, waves=8, cg=1, rows_w=4, t=3, splits=2),  # two workgroups share the channels
+    dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=3),  # 6 blocks in three parts
+    dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=6),  # one block each
+]
+
+
+@pytest.mark.parametrize("plan", EPILOGUE_PLANS, ids=[str(i) for i in range(len(EPILOGUE_PLANS))])
+def test_bias_and_relu_epilogue(oracle, plan):
+    x, w = rand_case(MID, 10, 0.2, seed=71)
+    w[5] = 0   # a row with no nonzeros: its outputs are max(bias, 0)
+    rng = np.random.default_rng(72)
+    bias = (rng.standard_normal(MID.K) * 0.05).astype(np.float32)
+    for b, relu in ((bias, True), (bias, False), (None, True)):
+        info = check_fused(MID, w, x, oracle, plan, b, relu, what="epilogue")
+        if plan:
+            assert {k: info["plan"][k] for k in plan} == plan
+
+
+@pytest.mark.parametrize("splits", [2, 5])
+def test_channel_splits_without_epilogue(oracle, splits):
+    """Partial sums of several workgroups added with atomics: the plain entry point, a strip layout, a ragged batch."""
+    plan = dict(kernel=3, nt=4, cb=1, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9, splits=splits)
+    x, w = rand_case(BIG, 6, 0.2, seed=73)
+    _, info = check(BIG, w, x, oracle, plan, what="splits")
+    assert info["plan"]["splits"] == splits

@@ -92,6 +92,7 @@ PLANS = [
     dict(kernel=3, nt=4, cb=6, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9),   # 3 strips of 9 columns for 13
     dict(kernel=3, nt=4, cb=6, waves=8, cg=2, rows_w=6, t=3, band=13, strip=9),  # two waves stacked: 14 rows
     dict(kernel=3, nt=4, cb=4, waves=4, cg=1, rows_w=2, t=7, band=8, strip=8),
+    dict(kernel=3, nt=4, cb=3, waves=4, cg=1, rows_w=8, t=3, splits=3),          # channel blocks shared by 3 workgroups
 ]
 
 
@@ -104,7 +105,7 @@ def test_explicit_plans_round_trip(oracle, plan):
     o_off = oracle.lower_offsets(layer, o_rowptr, o_col)
     h = B.sconv_create_csr(layer, w, plan)
     got = B.sconv_csr_info(h)["plan"]
-    assert got == {**dict(band=layer.OH, strip=0), **plan}
+    assert got == {**dict(band=layer.OH, strip=0, splits=1), **plan}
     r, o, v = B.sconv_csr_unpack(h, 1)
     assert np.array_equal(r, o_rowptr) and np.array_equal(o, o_off)
     assert np.array_equal(v.view(np.uint32), o_val.view(np.uint32))

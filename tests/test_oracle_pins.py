@@ -225,3 +225,24 @@ def test_planted_mistakes_are_caught(oracle):
     out_t, _, _ = oracle.sparse_conv(layer, np.ascontiguousarray(w.transpose(0, 1, 3, 2)), x)
     out_f, _, _ = oracle.sparse_conv(layer, np.ascontiguousarray(w[:, :, ::-1, ::-1]), x)
     assert np.max(np.abs(out - out_t)) > 1e-3 and np.max(np.abs(out - out_f)) > 1e-3
+
+
+def test_bias_relu_epilogue_equals_library_layers(oracle):
+    """The epilogue oracle against torch's conv2d(bias) + relu in fp64; a bias on the wrong axis or a clamp
+    before the bias would fail (bias values straddle the outputs' range)."""
+    layer = wl.small_layer(C=6, H=9, W=7, K=8, R=3, S=3, stride=1, pad=1, groups=2)
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((3, layer.C, layer.H, layer.W)).astype(np.float32)
+    w = np.where(rng.random((layer.K, layer.Cg, 3, 3)) < 0.4, rng.standard_normal((layer.K, layer.Cg, 3, 3)), 0).astype(np.float32)
+    bias = (rng.standard_normal(layer.K) * 2).astype(np.float32)
+    ref, ab, _ = oracle.sparse_conv(layer, w, x)
+    for b, relu in ((bias, True), (bias, False), (None, True), (None, False)):
+        got, scale = oracle.bias_relu(ref, ab, b, relu)
+        t = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                       torch.from_numpy(b).double() if b is not None else None, 1, 1, 1, layer.groups)
+        if relu:
+            t = torch.relu(t)
+        assert np.allclose(got, t.numpy(), rtol=0, atol=1e-12)
+        assert np.all(scale >= ab) and (b is None) == bool(np.array_equal(scale, ab))
+    got, _ = oracle.bias_relu(ref, ab, bias, True)
+    assert (got == 0).any() and (got > 0).any()
