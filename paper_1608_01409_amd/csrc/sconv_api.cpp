@@ -36,7 +36,7 @@ static const LdsTiling &f_tiling(const sconv_csr *h) { return h->lds_flat.t; }
 static bool same_plan(const sconv_plan &a, const sconv_plan &b)
 {
     return a.kernel == b.kernel && a.nt == b.nt && a.cb == b.cb && a.waves == b.waves && a.cg == b.cg &&
-           a.rows_w == b.rows_w && a.t == b.t && a.band == b.band;
+           a.rows_w == b.rows_w && a.t == b.t && a.band == b.band && a.strip == b.strip && a.splits == b.splits;
 }
 
 // Choose (or re-choose) the LDS tiling for batch size n and pack for it.  The best tiling depends on the

@@ -237,20 +237,28 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
 static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, double avg_row_nnz)
 {
     const Geometry g = geometry(d);
-    const double wgs = (double)ceil_div(N, 4) * d.groups * t.nkt * t.n_bands;
+    const int splits = std::max(1, t.p.splits);
+    const int blocks = ceil_div(t.nblk, splits);              // channel blocks one workgroup walks
+    const double wgs = (double)ceil_div(N, 4) * d.groups * t.nkt * t.n_bands * splits;
     const int by_lds = std::max(1, (160 * 1024) / (t.lds_bytes + 512));
     const int wpc = std::max(1, std::min(by_lds, 16 / t.p.waves));
     const double rows_wave = (double)g.Kg / (t.nkt * t.rg);
-    const double entries = rows_wave * avg_row_nnz + 3.5 * t.nblk;
+    const double entries = rows_wave * avg_row_nnz / splits + 3.5 * blocks;
     const double cu_wgs = std::ceil(wgs / 256.0);             // workgroups one CU has to run ...
     const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
     const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
     double eff = wps >= 4 ? 0.78 : wps >= 3 ? 0.72 : wps >= 2 ? 0.68 : 0.42;
     if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.86; // shallow read-ahead ring
     const double simd_clk = t.p.waves * entries * (4.0 * t.p.t + 1.7); // VALU clocks per SIMD, one workgroup
-    double group = m * simd_clk / eff + t.nblk * 1500.0 + 14000.0;
+    double group = m * simd_clk / eff + blocks * 1500.0 + 14000.0;
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
-    return std::ceil(cu_wgs / m) * group / 2400.0;
+    double us = std::ceil(cu_wgs / m) * group / 2400.0;
+    if (splits > 1) {
+        // the output is zeroed by a launch of its own and every part adds to it with atomics
+        const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
+        us += 4.0 + out_bytes / 3.0e6 + out_bytes * splits / 3.0e6;
+    }
+    return us;
 }
 
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
@@ -297,14 +305,21 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                     if (cb < 1) continue;
                     // even out the blocks
                     if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
-                    sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip, req.splits};
-                    LdsTiling t;
-                    if (fill_tiling(d, p, t) != SCONV_OK) continue;
-                    const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
-                                               : tiling_cost(d, t, N_hint, avg_row_nnz);
-                    if (best < 0 || c < best) {
-                        best = c;
-                        out = t;
+                    // channel blocks of a tile shared by several workgroups, when there are too few tiles
+                    static const int split_choices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+                    for (int sp : split_choices) {
+                        if (req.splits ? sp != 1 : (sp > 1 && kind != 3)) continue;
+                        const int splits = req.splits ? req.splits : sp;
+                        sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip, splits};
+                        LdsTiling t;
+                        if (fill_tiling(d, p, t) != SCONV_OK) continue;
+                        if (!req.splits && t.p.splits != sp) continue; // the same as a smaller choice
+                        const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
+                                                   : tiling_cost(d, t, N_hint, avg_row_nnz);
+                        if (best < 0 || c < best) {
+                            best = c;
+                            out = t;
+                        }
                     }
                 }
             }
