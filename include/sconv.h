@@ -35,7 +35,7 @@ typedef enum {
     SCONV_ERR_NULL = -1,        /* a required pointer is NULL */
     SCONV_ERR_DESC = -2,        /* non-positive size, groups not dividing C or K, output smaller than 1x1 */
     SCONV_ERR_CSR = -3,         /* rowptr not starting at 0 / not monotone, column out of range or not strictly ascending */
-    SCONV_ERR_BATCH = -4,       /* N < 1 */
+    SCONV_ERR_BATCH = -4,       /* N < 1; sconv_fc_forward: N not a multiple of 4 (per tile of 1024) */
     SCONV_ERR_CAPACITY = -5,    /* caller's buffer too small (export) */
     SCONV_ERR_PLAN = -6,        /* a tiling the kernels cannot run was requested */
     SCONV_ERR_HIP = -7,         /* a HIP call failed; sconv_last_hip_error() has its code */
@@ -65,10 +65,9 @@ typedef struct {
  * a wave are t such blocks side by side (t*w >= OW, band <= cg * (64/w)),
  * which wastes fewer lanes when OW is a little under t*w.  `splits` (kernel 3
  * only; 0 or 1 = none): that many workgroups share the channel blocks of a
- * tile and add their partial sums to the zeroed output with floating-point
- * atomics, for launches that would otherwise leave compute units idle; the
- * order of those additions, and so the last bits of the result, can differ
- * from run to run.
+ * tile, for launches that would otherwise leave compute units idle; each
+ * stores its partial results into scratch memory the handle owns and a second
+ * launch adds them up in a fixed order.
  */
 typedef struct {
     int32_t kernel, nt, cb, waves, cg, rows_w, t, band, strip, splits;
@@ -131,9 +130,9 @@ int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hi
  * evaluates (Section 3) apply both after every convolution, and fusing them
  * saves a pass over the output.  `bias` [device] holds K
  * floats or is NULL (none); relu != 0 clamps at zero.  The flat-stream kernel
- * applies both to its accumulators; the other kernels, and launches that split
- * the channels over workgroups, run an elementwise pass of their own after the
- * convolution.
+ * applies both to its accumulators; the other kernels run an elementwise pass
+ * of their own after the convolution, and launches that split the channels
+ * over workgroups apply them while adding up the partial results.
  */
 int sconv_forward_fused(sconv_csr *h, const float *in, float *out, int32_t N, const float *bias, int32_t relu,
                         void *hip_stream);
@@ -144,6 +143,27 @@ int sconv_last_hip_error(const sconv_csr *h);
 void sconv_destroy_csr(sconv_csr *h);
 
 const char *sconv_strerror(int status);
+
+/* ---- fully connected layers as sparse x dense matrix products (end of Section 2.1) ---- */
+
+/*
+ * out_t[K][N] = W x in_t[C][N]: W is the CSR matrix of a handle created for a
+ * layer with H = W = R = S = 1, stride 1, pad 0, groups 1 (weights [K][C];
+ * SCONV_ERR_DESC otherwise), the activations are feature-major, both [device],
+ * contiguous fp32, one row of N images per feature.  N must be a multiple of
+ * 4, and of 4 * ceil(N / 1024) above 1024 (SCONV_ERR_BATCH).  `bias` [device,
+ * K floats] may be NULL; relu != 0 clamps at zero.  The same kernel as the
+ * convolution's runs it: a feature's row is a channel plane, four consecutive
+ * images one cell, the rows of W are register-blocked per wave and the features
+ * walked in blocks staged through LDS, shared by several workgroups when K
+ * alone gives too few (`splits` of the plan).  The arrays are packed for N on
+ * the first call with that N.  `out_t` is overwritten; enqueued on `hip_stream`.
+ */
+int sconv_fc_forward(sconv_csr *h, const float *in_t, float *out_t, int32_t N, const float *bias, int32_t relu,
+                     void *hip_stream);
+
+/* The tiling sconv_fc_forward uses for batch N (packs for it if it has not yet). */
+int sconv_fc_plan(sconv_csr *h, int32_t N, sconv_plan *plan);
 
 /* ---- roofline performance model (Section 2.2) ------------------------------ */
 

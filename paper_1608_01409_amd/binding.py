@@ -49,7 +49,8 @@ class sconv_balance(C.Structure):
 
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
-           "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance"]
+           "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance",
+           "sconv_fc_forward", "sconv_fc_plan"]
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
@@ -74,6 +75,8 @@ def lib():
         L.sconv_csr_unpack.argtypes = [vp, i32, vp, vp, vp, i64p]
         L.sconv_forward.argtypes = [vp, vp, vp, i32, vp]
         L.sconv_forward_fused.argtypes = [vp, vp, vp, i32, vp, i32, vp]
+        L.sconv_fc_forward.argtypes = [vp, vp, vp, i32, vp, i32, vp]
+        L.sconv_fc_plan.argtypes = [vp, i32, C.POINTER(sconv_plan)]
         L.sconv_last_hip_error.argtypes = [vp]
         L.sconv_destroy_csr.argtypes = [vp]
         L.sconv_destroy_csr.restype = None
@@ -232,6 +235,40 @@ def sconv_forward_fused(csr: Csr, x, bias=None, relu=False, out=None, stream=Non
     if rc != SCONV_OK:
         raise SconvError(rc, f"sconv_forward_fused (hip error {lib().sconv_last_hip_error(csr.handle)})")
     return out
+
+
+def fc_layer(C_in: int, K: int):
+    """The layer description of a fully connected layer with weights [K][C_in]."""
+    from .workloads import Layer
+    return Layer(f"fc{C_in}x{K}", C_in, 1, 1, K, 1, 1, 1, 0, 1)
+
+
+def sconv_fc_plan(csr: Csr, N: int) -> dict:
+    p = sconv_plan()
+    _check(lib().sconv_fc_plan(csr.handle, N, C.byref(p)), "sconv_fc_plan")
+    return p.as_dict()
+
+
+def sconv_fc_forward(csr: Csr, x_t, bias=None, relu=False, out_t=None, stream=None):
+    """x_t: contiguous fp32 CUDA tensor [C][N] (feature-major); returns/overwrites out_t [K][N]."""
+    import torch
+
+    L = csr.layer
+    assert x_t.is_cuda and x_t.dtype == torch.float32 and x_t.is_contiguous() and x_t.dim() == 2 and x_t.shape[0] == L.C
+    N = x_t.shape[1]
+    if out_t is None:
+        out_t = torch.empty((L.K, N), dtype=torch.float32, device=x_t.device)
+    assert out_t.is_cuda and out_t.dtype == torch.float32 and out_t.is_contiguous() and tuple(out_t.shape) == (L.K, N)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and tuple(bias.shape) == (L.K,)
+    s = stream if stream is not None else torch.cuda.current_stream(x_t.device)
+    with torch.cuda.device(x_t.device):
+        rc = lib().sconv_fc_forward(csr.handle, C.c_void_p(x_t.data_ptr()), C.c_void_p(out_t.data_ptr()), N,
+                                    C.c_void_p(bias.data_ptr()) if bias is not None else None, int(bool(relu)),
+                                    C.c_void_p(s.cuda_stream))
+    if rc != SCONV_OK:
+        raise SconvError(rc, f"sconv_fc_forward (hip error {lib().sconv_last_hip_error(csr.handle)})")
+    return out_t
 
 
 def sconv_machine_gfx950() -> sconv_machine:

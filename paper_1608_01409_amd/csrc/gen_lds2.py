@@ -59,8 +59,8 @@ OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride 
 
 OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase", "slab0", "slabstep", "nslab",
        "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff", "outp_hi", "nch", "nblk", "bias", "flags"]
-FLAG_RELU, FLAG_ATOMIC = 0, 1   # bits of the flags operand
-OP = {n: f"%{i}" for i, n in enumerate(OPS)}
+FLAG_RELU = 0                  # bit of the flags operand
+OP = {n: f"%[{n}]" for n in OPS}
 
 
 def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
@@ -294,20 +294,12 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
                     emit(f"{instr} v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
                 emit(f"{rowend}:")
 
-    # a workgroup that holds only part of the input channels adds its partial sums to a zeroed output
-    plain, done = label("plain"), label("stored")
-    emit(f"s_bitcmp1_b32 {OP['flags']}, {FLAG_ATOMIC}")
-    emit(f"s_cbranch_scc0 {plain}")
-    store_all("global_atomic_add_f32")
-    emit(f"s_branch {done}")
-    emit(f"{plain}:")
     store_all("global_store_dword")
-    emit(f"{done}:")
     emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
 
-    ins = ('"s"(kern), "s"(rsrc), "s"(segp), "s"(rowp), "s"(outp_lo), "s"(soff0), "s"(nimg), "s"(lim), "s"(ldsbase), '
-           '"s"(slab0), "s"(slabstep), "s"(nslab), "v"(lane_byte), "v"(voff0), "v"(voff1), "v"(voff2), "v"(voff3), '
-           '"v"(tbloff), "s"(outp_hi), "s"(nch), "s"(nblk), "s"(bias), "s"(flags)')
+    vregs = {"lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff"}
+    cnames = {"outp": "outp_lo"}
+    ins = ", ".join(f'[{n}] "{"v" if n in vregs else "s"}"({cnames.get(n, n)})' for n in OPS)
     text = []
     for ins_ in L:
         text.append(f'            "{ins_}\\n\\t"')

@@ -27,11 +27,47 @@ struct sconv_csr {
     Canonical kcanon;        // filled only when phased
     void *phase_buf = nullptr;
     size_t phase_bytes = 0;
+    void *part_buf = nullptr; // partial results of launches that split the channels over workgroups
+    size_t part_bytes = 0;
     const Canonical &kc() const { return phased ? kcanon : canon; }
+    // fully connected use (sconv_fc_forward): the layer as a 1x1 convolution whose positions are the batch
+    int fc_n = 0;            // batch size the arrays below were packed for
+    int fc_tiles = 0;        // the batch is cut into this many tiles of fc_n / fc_tiles images
+    sconv_desc fc_desc;
+    PackedFlat fc_flat;
+    DeviceLds fc_dev;
+    bool fc_uploaded = false;
     int hip_err = 0;
 };
 
 static const LdsTiling &f_tiling(const sconv_csr *h) { return h->lds_flat.t; }
+
+// Scratch owned by the handle, grown on demand.
+static int grow(void **buf, size_t *have, size_t need, int *hip_err)
+{
+    if (need <= *have) return SCONV_OK;
+    release(*buf);
+    *buf = nullptr;
+    *have = 0;
+    const int rc = upload(nullptr, need, buf, hip_err);
+    if (rc) return rc;
+    *have = need;
+    return SCONV_OK;
+}
+
+// The flat-stream kernel and, when the tiling splits the channels, the reduction of its partial results.
+static int run_flat(sconv_csr *h, const sconv_desc &kd, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay,
+                    const float *in, float *out, int n_kernel, int64_t rows, int64_t inner, const Epilogue &ep, void *stream)
+{
+    if (t.p.splits <= 1) return launch_lds2(kd, t, dev, lay, in, out, n_kernel, ep, 0, stream, &h->hip_err);
+    const int64_t total = rows * inner;
+    int rc = grow(&h->part_buf, &h->part_bytes, (size_t)total * t.p.splits * sizeof(float), &h->hip_err);
+    if (rc) return rc;
+    float *parts = static_cast<float *>(h->part_buf);
+    rc = launch_lds2(kd, t, dev, lay, in, parts, n_kernel, ep, total, stream, &h->hip_err);
+    if (rc) return rc;
+    return launch_reduce(parts, out, t.p.splits, rows, inner, h->desc.K, ep, stream, &h->hip_err);
+}
 
 static bool same_plan(const sconv_plan &a, const sconv_plan &b)
 {
@@ -290,14 +326,8 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     if (use_lds && h->phased) {
         // re-order the input into phase images (scratch owned by the handle, grown on demand)
         const size_t need = (size_t)N * h->kdesc.C * h->kdesc.H * h->kdesc.W * sizeof(float);
-        if (need > h->phase_bytes) {
-            release(h->phase_buf);
-            h->phase_buf = nullptr;
-            h->phase_bytes = 0;
-            rc = upload(nullptr, need, &h->phase_buf, &h->hip_err);
-            if (rc) return rc;
-            h->phase_bytes = need;
-        }
+        rc = grow(&h->phase_buf, &h->phase_bytes, need, &h->hip_err);
+        if (rc) return rc;
         rc = launch_phase(h->desc, h->kdesc, in, static_cast<float *>(h->phase_buf), N, hip_stream, &h->hip_err);
         if (rc) return rc;
         in = static_cast<const float *>(h->phase_buf);
@@ -313,16 +343,7 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
             h->lds_uploaded = true;
         }
         const LdsTiling &ft = f_tiling(h);
-        const bool split = ft.p.splits > 1;
-        if (split) { // partial sums are added to a zeroed output
-            rc = launch_fill_zero(out, out_rows * out_inner, hip_stream, &h->hip_err);
-            if (rc) return rc;
-        }
-        rc = launch_lds2(h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, ep, hip_stream, &h->hip_err);
-        if (rc || !split || !ep.relu) return rc;
-        Epilogue clamp;
-        clamp.relu = true;
-        return launch_epilogue(out, out_rows, out_inner, h->desc.K, clamp, hip_stream, &h->hip_err);
+        return run_flat(h, h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, out_rows, out_inner, ep, hip_stream);
     }
     if (use_lds) {
         if (!h->lds_uploaded) {
@@ -345,6 +366,112 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     return rc ? rc : launch_epilogue(out, out_rows, out_inner, h->desc.K, ep, hip_stream, &h->hip_err);
 }
 
+// ---- fully connected layers: out_t[K][N] = W[K][C] (CSR) x in_t[C][N] -------------------------------
+//
+// With the activations feature-major, four consecutive images of one feature are exactly one LDS cell of
+// the flat-stream kernel and a feature's row is a channel plane: the product is the 1x1 convolution of a
+// C-channel "image" of N/4 positions x 4 images, and the kernel runs it unchanged through other strides.
+
+static bool is_fc(const sconv_desc &d)
+{
+    return d.H == 1 && d.W == 1 && d.R == 1 && d.S == 1 && d.stride == 1 && d.pad == 0 && d.groups == 1;
+}
+
+static void release_fc(sconv_csr *h)
+{
+    release(h->fc_dev.pairs);
+    release(h->fc_dev.seg_ptr);
+    release(h->fc_dev.row_of);
+    release(h->fc_dev.store_tbl);
+    h->fc_dev = DeviceLds();
+    h->fc_uploaded = false;
+}
+
+static int plan_fc(sconv_csr *h, int N)
+{
+    if (!is_fc(h->desc)) return SCONV_ERR_DESC;
+    if (N < 4 || N % 4) return SCONV_ERR_BATCH;
+    if (N == h->fc_n) return SCONV_OK;
+    // one wave covers at most 4 x 256 images; larger batches are cut into equal tiles
+    const int tiles = (N + 1023) / 1024;
+    if (N % (4 * tiles)) return SCONV_ERR_BATCH;
+    const int nc = N / tiles;
+    sconv_desc kd = h->desc;
+    kd.W = nc / 4;
+    Canonical kc;
+    kc.rowptr = h->canon.rowptr;
+    kc.colidx = h->canon.colidx;
+    kc.val = h->canon.val;
+    kc.off.resize(h->canon.off.size());
+    for (size_t j = 0; j < kc.off.size(); ++j) kc.off[j] = h->canon.off[j] * kd.W; // feature c = plane c of the wide image
+    sconv_plan req;
+    std::memset(&req, 0, sizeof(req));
+    req.kernel = 3;
+    req.nt = 4;
+    const double avg = kd.K ? (double)kc.val.size() / kd.K : 0.0;
+    LdsTiling t;
+    int rc = make_lds_tiling(kd, req, 4 * tiles, avg, t);
+    if (rc) return rc;
+    t.out_pos = 4; // the four images of a cell are consecutive in the output row
+    if (h->fc_uploaded) release_fc(h);
+    h->fc_n = 0;
+    rc = pack_flat(kd, kc, t, h->fc_flat);
+    if (rc) return rc;
+    h->fc_desc = kd;
+    h->fc_tiles = tiles;
+    h->fc_n = N;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_fc_plan(sconv_csr *h, int32_t N, sconv_plan *plan)
+{
+    if (!h || !plan) return SCONV_ERR_NULL;
+    try {
+        const int rc = plan_fc(h, N);
+        if (rc) return rc;
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    *plan = h->fc_flat.t.p;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_fc_forward(sconv_csr *h, const float *in_t, float *out_t, int32_t N, const float *bias, int32_t relu,
+                                void *hip_stream)
+{
+    if (!h || !in_t || !out_t) return SCONV_ERR_NULL;
+    if (N < 1) return SCONV_ERR_BATCH;
+    int rc;
+    try {
+        rc = plan_fc(h, N);
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    if (rc) return rc;
+    if (!h->fc_uploaded) {
+        const PackedFlat &f = h->fc_flat;
+        rc = upload(f.pairs.data(), f.pairs.size() * 8, &h->fc_dev.pairs, &h->hip_err);
+        if (!rc) rc = upload(f.seg.data(), f.seg.size() * 4, &h->fc_dev.seg_ptr, &h->hip_err);
+        if (!rc) rc = upload(f.row_of.data(), f.row_of.size() * 4, &h->fc_dev.row_of, &h->hip_err);
+        if (!rc) rc = upload(f.store_tbl.data(), f.store_tbl.size() * 4, &h->fc_dev.store_tbl, &h->hip_err);
+        if (rc) {
+            release_fc(h);
+            return rc;
+        }
+        h->fc_uploaded = true;
+    }
+    const LdsTiling &t = h->fc_flat.t;
+    const int64_t C = h->desc.C, K = h->desc.K, nc = N / h->fc_tiles;
+    Lds2Layout lay;
+    lay.in_tile = nc; lay.in_img = 1; lay.in_ch = N; lay.in_pos = 4;
+    lay.in_rec_fixed = C * N * 4; lay.in_rec_img = 0; lay.in_rec_tile = nc * 4;
+    lay.out_tile = nc; lay.out_band = 0; lay.out_row = N; lay.out_img = 1; lay.out_pos = 4;
+    Epilogue ep;
+    ep.bias = bias;
+    ep.relu = relu != 0;
+    return run_flat(h, h->fc_desc, t, h->fc_dev, lay, in_t, out_t, 4 * h->fc_tiles, K, N, ep, hip_stream);
+}
+
 extern "C" int sconv_last_hip_error(const sconv_csr *h) { return h ? h->hip_err : 0; }
 
 extern "C" void sconv_destroy_csr(sconv_csr *h)
@@ -355,6 +482,8 @@ extern "C" void sconv_destroy_csr(sconv_csr *h)
     release(h->dev_lds.row_of);
     release(h->dev_lds.store_tbl);
     release(h->phase_buf);
+    release(h->part_buf);
+    release_fc(h);
     release(h->dev_direct.rowptr);
     release(h->dev_direct.trip);
     delete h;
@@ -367,7 +496,7 @@ extern "C" const char *sconv_strerror(int status)
     case SCONV_ERR_NULL: return "a required pointer is NULL";
     case SCONV_ERR_DESC: return "bad layer descriptor";
     case SCONV_ERR_CSR: return "malformed CSR arrays";
-    case SCONV_ERR_BATCH: return "batch size must be at least 1";
+    case SCONV_ERR_BATCH: return "batch size below 1, or not one the fully connected path takes (a multiple of 4 per tile)";
     case SCONV_ERR_CAPACITY: return "output buffer too small";
     case SCONV_ERR_PLAN: return "tiling not runnable for this layer";
     case SCONV_ERR_HIP: return "HIP call failed";

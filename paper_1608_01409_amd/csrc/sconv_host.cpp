@@ -254,9 +254,9 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
     double us = std::ceil(cu_wgs / m) * group / 2400.0;
     if (splits > 1) {
-        // the output is zeroed by a launch of its own and every part adds to it with atomics
+        // every part stores its partial results and a launch of its own adds them up
         const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
-        us += 4.0 + out_bytes / 3.0e6 + out_bytes * splits / 3.0e6;
+        us += 4.0 + 2.0 * splits * out_bytes / 4.0e6;
     }
     return us;
 }
@@ -343,6 +343,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                 if (req.cg && req.cg != cg) continue;
                 const int T = ceil_div(n_chunks, cg);
                 if (req.t && req.t != T) continue;
+                if (!req.cg && (cg - 1) * T >= n_chunks) continue; // a wave of the column group without positions
                 try_shapes(nt, vec, band, cg, T, 0);
             }
             if (req.band) break;
@@ -530,7 +531,7 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
         }
     }
     if (real != c.val.size()) return SCONV_ERR_PLAN;
-    // the kernel prefetches two chunks past the segment it is working on
+    // the kernel loads two chunks past the segment it is working on
     for (int i = 0; i < 3 * SCONV_FLAT_CHUNK; ++i) out.pairs.push_back(pad_entry);
     // store offsets of the positions a group of cg waves covers
     const int npos = t.p.cg * t.p.t * 64;

@@ -147,15 +147,19 @@ struct Epilogue {
 // q*out_pos.  nchw_layout() gives the convolution's [N][C][H][W] -> [N][K][OH][OW].
 struct Lds2Layout {
     int64_t in_tile, in_img, in_ch, in_pos;
-    int64_t in_rec_fixed, in_rec_img; // bytes a tile with n valid images may read: in_rec_fixed + n * in_rec_img
+    int64_t in_rec_fixed, in_rec_img, in_rec_tile; // bytes tile m with n valid images may read: fixed + n * img - m * tile
     int64_t out_tile, out_band, out_row, out_img, out_pos;
 };
 Lds2Layout nchw_layout(const sconv_desc &d, const LdsTiling &t);
+// With t.p.splits > 1 `out` is a workspace of splits * split_stride floats that receives each part's partial
+// results in the output's layout, and launch_reduce adds them up (and applies the epilogue) afterwards.
 int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay, const float *in,
-                float *out, int N, const Epilogue &ep, void *stream, int *hip_err);
+                float *out, int N, const Epilogue &ep, int64_t split_stride, void *stream, int *hip_err);
+int launch_reduce(const float *parts, float *out, int splits, int64_t rows, int64_t inner, int K, const Epilogue &ep,
+                  void *stream, int *hip_err);
 // out[n][k][..] = max(out + bias[k], 0) in place, for the paths that do not fuse it: rows of `inner` floats
 int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilogue &ep, void *stream, int *hip_err);
-int launch_fill_zero(float *out, int64_t n, void *stream, int *hip_err);
+
 // in [N][C][H][W] -> q [N][C*s*s][Hq][Wq], zero padding written out
 int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, float *q, int N, void *stream, int *hip_err);
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,

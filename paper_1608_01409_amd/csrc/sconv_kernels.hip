@@ -63,10 +63,19 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
 
     // Consecutive workgroup ids land on different XCDs (each with its own L2); the workgroups that
     // share one image tile (same input, different rows) are given ids 8 apart so they meet in one L2.
+    // workgroup id -> (image tile, unit): tiles 8 at a time, one per XCD; leftover tiles spread over all XCDs
     const int bid = blockIdx.x;
-    const int xcd = bid & 7, slot = bid >> 3;
-    const int unit = slot % a.units;
-    const int tile = (slot / a.units) * 8 + xcd;
+    const int full = (a.n_tiles >> 3) * 8 * a.units;
+    int unit, tile;
+    if (bid < full) {
+        const int xcd = bid & 7, slot = bid >> 3;
+        unit = slot % a.units;
+        tile = (slot / a.units) * 8 + xcd;
+    } else {
+        const int j = bid - full;
+        tile = (a.n_tiles >> 3) * 8 + j / a.units;
+        unit = j % a.units;
+    }
     if (tile >= a.n_tiles) return;
     const int gk = unit / a.n_bands, band_i = unit - gk * a.n_bands;
     const int g = gk / a.nkt, kt = gk - g * a.nkt;
@@ -214,11 +223,12 @@ struct Lds2Args {
     // image) sits at tile * in_tile + i * in_img + c * (HW4 / 4) + (Y * W + X) * in_pos
     long long in_tile;
     int in_img, in_pos;
-    long long in_rec_fixed, in_rec_img; // a tile with n valid images may read in_rec_fixed + n * in_rec_img bytes; past that, 0
+    long long in_rec_fixed, in_rec_img, in_rec_tile; // tile m with n valid images may read in_rec_fixed + n * in_rec_img - m * in_rec_tile bytes; past that, 0
     long long out_tile;      // floats from one tile's outputs to the next
     int out_band;            // floats from one band's outputs to the next (band * OW for NCHW)
     int out_pos4;            // bytes from one output position to the next (4 for NCHW); the store table holds multiples
     int splits, blk_split;   // workgroups along the input channels, channel blocks each of them takes
+    long long split_stride;  // floats from one part's partial results to the next (out then is the workspace)
     const float *bias;       // [K] added to every output of row k, or null
     int relu;                // outputs below zero become zero
 };
@@ -244,10 +254,22 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_waves = (int)blockDim.x >> 6;
 
+    // Workgroup ids go round the 8 XCDs (each with its own L2).  Image tiles are taken 8 at a time, one per
+    // XCD, so that the workgroups that stage the same input for different rows, bands and channel parts
+    // meet in one L2; the tiles left over when their number is not a multiple of 8 are spread over all
+    // XCDs unit by unit, so that a launch with few tiles still uses the whole chip.
     const int bid = blockIdx.x;
-    const int xcd = bid & 7, slot = bid >> 3;
-    const int unit = slot % a.units;
-    const int tile = (slot / a.units) * 8 + xcd;
+    const int full = (a.n_tiles >> 3) * 8 * a.units;
+    int unit, tile;
+    if (bid < full) {
+        const int xcd = bid & 7, slot = bid >> 3;
+        unit = slot % a.units;
+        tile = (slot / a.units) * 8 + xcd;
+    } else {
+        const int j = bid - full;
+        tile = (a.n_tiles >> 3) * 8 + j / a.units;
+        unit = j % a.units;
+    }
     if (tile >= a.n_tiles) return;
     const int us = unit / a.splits, split = unit - us * a.splits;
     const int gk = us / a.n_bands, band_i = us - gk * a.n_bands;
@@ -302,9 +324,10 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     int4v rsrc;
     rsrc.x = __builtin_amdgcn_readfirstlane((int)(unsigned)ip);
     rsrc.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(ip >> 32));   // stride 0
-    rsrc.z = __builtin_amdgcn_readfirstlane((int)(a.in_rec_fixed + a.in_rec_img * nimg)); // bytes past which loads return 0
+    rsrc.z = __builtin_amdgcn_readfirstlane((int)(a.in_rec_fixed + a.in_rec_img * nimg - a.in_rec_tile * tile)); // bytes past which loads return 0
     rsrc.w = 0x00020000;                                                   // raw 32-bit data format
-    const unsigned long long op = (unsigned long long)(a.out + (size_t)tile * a.out_tile + (size_t)band_i * a.out_band);
+    const unsigned long long op = (unsigned long long)(a.out + (size_t)split * a.split_stride + (size_t)tile * a.out_tile +
+                                                       (size_t)band_i * a.out_band);
     const unsigned lim = (unsigned)(min(a.band, a.OH - y0) * a.OW * a.out_pos4);
     const unsigned ldsbase = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void *)smem4;
     // cell of the plane this lane's chunk 0 sits on; chunk t is STEP cells further.  Flat: position p is
@@ -319,12 +342,8 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         cell0 = y * a.Wl + bx;
         if (by >= a.strip_rows || y >= a.band) cell0 &= 15;
     }
-    // the first split adds the bias
-    const unsigned long long bias_all = (unsigned long long)a.bias;
-    const unsigned bias_lo = (unsigned)__builtin_amdgcn_readfirstlane(split == 0 ? (int)(unsigned)bias_all : 0);
-    const unsigned bias_hi = (unsigned)__builtin_amdgcn_readfirstlane(split == 0 ? (int)(unsigned)(bias_all >> 32) : 0);
-    const unsigned long long bias = ((unsigned long long)bias_hi << 32) | bias_lo;
-    const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane((a.relu ? 1 : 0) | (a.splits > 1 ? 2 : 0));
+    const unsigned long long bias = (unsigned long long)a.bias;
+    const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane(a.relu ? 1 : 0);
     Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
                        a.seg + ((size_t)wslot * a.nblk + blk0) * 2,
                        a.row_of + (size_t)wslot * R,
@@ -451,7 +470,7 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
     if ((t.n_slabs + t.p.waves - 1) / t.p.waves > kMaxSlabsPerWave) return SCONV_ERR_PLAN;
     if ((int64_t)t.p.nt * d.C * d.H * d.W >= ((int64_t)1 << 29)) return SCONV_ERR_RANGE;
     if (t.lds_bytes % 16 || t.lds_bytes > 160 * 1024) return SCONV_ERR_PLAN;
-    const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
+    const int64_t grid64 = (int64_t)a.n_tiles * a.units;
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -515,11 +534,17 @@ __global__ void __launch_bounds__(256) sconv_epilogue_kernel(float *out, const f
     out[i] = v;
 }
 
-__global__ void __launch_bounds__(256) sconv_fill_zero_kernel(float4 *out4, float *tail, long long n4, int n_tail)
+// out = sum of the parts' partial results (+ bias, ReLU): four floats per thread where the alignment allows.
+__global__ void __launch_bounds__(256) sconv_reduce_kernel(const float *parts, float *out, int splits, long long total,
+                                                           long long inner, int K, const float *bias, int relu)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i < n4) out4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n_tail) tail[i] = 0.f;
+    if (i >= total) return;
+    float v = 0.f;
+    for (int s2 = 0; s2 < splits; ++s2) v += parts[(long long)s2 * total + i];
+    if (bias) v += bias[(int)((i / inner) % K)];
+    if (relu) v = fmaxf(v, 0.f);
+    out[i] = v;
 }
 
 int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilogue &ep, void *stream, int *hip_err)
@@ -537,14 +562,13 @@ int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilog
     return SCONV_OK;
 }
 
-// A fill kernel rather than a memset node: safe to record into a graph the caller captures.
-int launch_fill_zero(float *out, int64_t n, void *stream, int *hip_err)
+int launch_reduce(const float *parts, float *out, int splits, int64_t rows, int64_t inner, int K, const Epilogue &ep,
+                  void *stream, int *hip_err)
 {
-    if (((uintptr_t)out & 15) != 0) return SCONV_ERR_PLAN; // device allocations are 256-byte aligned
-    const int64_t n4 = n / 4, gx = (std::max<int64_t>(n4, 1) + 255) / 256;
+    const int64_t total = rows * inner, gx = (total + 255) / 256;
     if (gx > 0x7fffffff) return SCONV_ERR_RANGE;
-    hipLaunchKernelGGL(sconv_fill_zero_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       reinterpret_cast<float4 *>(out), out + n4 * 4, (long long)n4, (int)(n - n4 * 4));
+    hipLaunchKernelGGL(sconv_reduce_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream), parts, out, splits,
+                       (long long)total, (long long)inner, K, ep.bias, ep.relu ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         *hip_err = (int)e;
@@ -559,13 +583,13 @@ Lds2Layout nchw_layout(const sconv_desc &d, const LdsTiling &t)
     Lds2Layout l;
     const int64_t HW = (int64_t)d.H * d.W, OHW = (int64_t)g.OH * g.OW;
     l.in_img = d.C * HW; l.in_tile = 4 * l.in_img; l.in_ch = HW; l.in_pos = 1;
-    l.in_rec_fixed = 0; l.in_rec_img = l.in_img * 4;
+    l.in_rec_fixed = 0; l.in_rec_img = l.in_img * 4; l.in_rec_tile = 0;
     l.out_img = d.K * OHW; l.out_tile = 4 * l.out_img; l.out_band = (int64_t)t.p.band * g.OW; l.out_row = OHW; l.out_pos = 1;
     return l;
 }
 
 int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay, const float *in,
-                float *out, int N, const Epilogue &ep, void *stream, int *hip_err)
+                float *out, int N, const Epilogue &ep, int64_t split_stride, void *stream, int *hip_err)
 {
     const Geometry g = geometry(d);
     Lds2Args a;
@@ -590,8 +614,11 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     a.page_bytes = t.page_cells * 16;
     a.strip = t.p.strip; a.strip_rows = t.strip_rows;
     a.n_bufs = t.n_bufs;
-    a.bias = ep.bias;
-    a.relu = (ep.relu && a.splits == 1) ? 1 : 0;   // partial sums cannot be clamped: a pass of its own follows
+    // with several parts the kernel stores partial sums into the workspace `out` points to, part after part,
+    // and the reduction that follows applies the epilogue
+    a.split_stride = a.splits > 1 ? split_stride : 0;
+    a.bias = a.splits == 1 ? ep.bias : nullptr;
+    a.relu = (ep.relu && a.splits == 1) ? 1 : 0;
     // offsets the kernel keeps in 32 bits
     const int64_t lim32 = (int64_t)1 << 31;
     if (lay.in_img * 4 * 4 >= lim32 || lay.in_ch * 4 >= lim32 || lay.in_pos * 4 * d.H * d.W >= lim32) return SCONV_ERR_RANGE;
@@ -600,7 +627,8 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     if ((int64_t)t.p.band * g.OW * lay.out_pos * 4 >= lim32) return SCONV_ERR_RANGE;
     a.in_tile = lay.in_tile; a.in_img = (int)lay.in_img; a.in_pos = (int)lay.in_pos; a.HW4 = (int)(lay.in_ch * 4);
     if (lay.in_rec_fixed + 4 * lay.in_rec_img >= lim32) return SCONV_ERR_RANGE;
-    a.in_rec_fixed = lay.in_rec_fixed; a.in_rec_img = lay.in_rec_img;
+    a.in_rec_fixed = lay.in_rec_fixed; a.in_rec_img = lay.in_rec_img; a.in_rec_tile = lay.in_rec_tile;
+    if (lay.in_rec_fixed - lay.in_rec_tile * (a.n_tiles - 1) < 0) return SCONV_ERR_RANGE;
     a.out_tile = lay.out_tile; a.out_band = (int)lay.out_band; a.OHW4 = (int)(lay.out_row * 4);
     a.out_pos4 = (int)(lay.out_pos * 4);
     // what the kernel assumes, checked before anything is launched
@@ -610,7 +638,7 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     if (a.block_bytes + a.page_bytes > a.buf_stride_bytes) return SCONV_ERR_PLAN;
     if (t.p.rows_w * t.p.t * 4 > 256) return SCONV_ERR_PLAN;
     a.img_stride_bytes = (int)(lay.out_img * 4);
-    const int64_t grid64 = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.units;
+    const int64_t grid64 = (int64_t)a.n_tiles * a.units;
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;
     hipStream_t s = static_cast<hipStream_t>(stream);

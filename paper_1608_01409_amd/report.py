@@ -4,7 +4,7 @@ roofline model's prediction and the dense-convolution crossover (Section 2.2,
 Section 3.2 / Figure 5 of the paper), the skewed guided-pruning-like patterns,
 and the GoogLeNet-like and strided layers.
 
-    python -m paper_1608_01409_amd.report sweep|skewed|extra|onebyone|all [--iters K]
+    python -m paper_1608_01409_amd.report sweep|skewed|extra|onebyone|fc|all [--iters K]
 
 Every input is seeded and synthetic (paper_1608_01409_amd/workloads.py).  The
 dense reference is the vendor's fp32 convolution reached through
@@ -159,9 +159,32 @@ def report_extra(iters, cfg=4, title="# GoogLeNet-inception-like and strided lay
         emit(row)
 
 
+def report_fc(iters):
+    print("# fully connected layers of AlexNet as sparse x dense products (feature-major activations)")
+    for i, (name, N, dens) in enumerate(wl.FC_CONFIG):
+        C_in, K = wl.FC_LAYERS[name]
+        x_t, w = wl.make_fc_case(i, name, N, dens)
+        xd = torch.from_numpy(x_t).cuda()
+        h = B.sconv_create_csr(B.fc_layer(C_in, K), w.reshape(K, C_in, 1, 1), dict(kernel=2))
+        out = torch.empty((K, N), dtype=torch.float32, device="cuda")
+        ms = time_gpu(lambda: B.sconv_fc_forward(h, xd, None, False, out), iters)
+        wd = torch.from_numpy(w).cuda()
+        torch.backends.cuda.matmul.allow_tf32 = False
+        ms_dense = time_gpu(lambda: torch.matmul(wd, xd), iters, warm=5)
+        nnz = int(np.count_nonzero(w))
+        flops = 2.0 * nnz * N
+        plan = B.sconv_fc_plan(h, N)
+        row = dict(report="fc", layer=name, N=N, density=dens, nnz=nnz, t_us=ms * 1e3, tflops=flops / ms / 1e9,
+                   t_dense_us=ms_dense * 1e3, dense_tflops=2.0 * K * C_in * N / ms_dense / 1e9, speedup=ms_dense / ms,
+                   weight_gb_per_s=8.0 * nnz / (ms * 1e-3) / 1e9, plan=plan)
+        print(f"{name}: N {N} x {dens} nnz {nnz}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s, dense fp32 matmul {ms_dense*1e3:.1f} us "
+              f"({row['dense_tflops']:.1f} TFLOP/s), speedup {ms_dense/ms:.2f}, plan {plan}")
+        emit(row)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["sweep", "skewed", "extra", "onebyone", "all"])
+    ap.add_argument("what", choices=["sweep", "skewed", "extra", "onebyone", "fc", "all"])
     ap.add_argument("--iters", type=int, default=20)
     args = ap.parse_args()
     if not torch.cuda.is_available():
@@ -177,6 +200,8 @@ def main() -> int:
     if args.what in ("onebyone", "all"):
         report_extra(args.iters, 5, "# 1x1 layers of inception modules, batch 64: Section 2.2 predicts no useful sparsity range "
                                     "when x_upper >= x_lower")
+    if args.what in ("fc", "all"):
+        report_fc(args.iters)
     return 0
 
 

@@ -77,6 +77,23 @@ CONFIGS = {
     4: [("goog3x3", 64, 0.20), ("goog5x5", 64, 0.30), ("conv1", 64, 0.30)],
     5: [("goog1x1_reduce", 64, 0.30), ("goog1x1", 64, 0.30)],   # beyond the benchmark configurations
 }
+# Fully connected layers of AlexNet (input features, output features), batch, density: the sparse x dense
+# products the paper's discussion of fully connected layers is about (end of Section 2.1).
+FC_LAYERS = {"fc6": (9216, 4096), "fc7": (4096, 4096), "fc8": (4096, 1000)}
+FC_CONFIG = [("fc6", 256, 0.10), ("fc7", 256, 0.10), ("fc8", 256, 0.25), ("fc7", 1024, 0.10)]
+
+
+def make_fc_case(index: int, name: str, N: int, density: float):
+    """(x_t [C][N] feature-major activations, w [K][C] pruned weights), seeded like make_case."""
+    C_in, K = FC_LAYERS[name]
+    rng_x, rng_m, rng_v = _streams(6, index)
+    x_t = rng_x.standard_normal((C_in, N), dtype=np.float32)
+    w = (rng_v.standard_normal((K, C_in), dtype=np.float32) * np.float32(WEIGHT_STD))
+    if density < 1.0:
+        w = np.where(rng_m.random((K, C_in)) < density, w, np.float32(0)).astype(np.float32)
+    return x_t, w
+
+
 SWEEP_DENSITIES = (0.01, 0.02, 0.05, 0.1, 0.2, 0.3, 0.5, 1.0)
 WEIGHT_STD = 0.01
 

@@ -337,7 +337,7 @@ EPILOGUE_PLANS = [
     dict(kernel=3, nt=4, cb=8, waves=8, cg=1, rows_w=6, t=3),            # fused
     dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=16, t=1, band=4),   # 16 rows per wave
     dict(kernel=3, nt=4, cb=7, waves=4, cg=1, rows_w=12, t=2, band=9),
-    dict(kernel=3, nt=4, cb=4, waves=8, cg=1, rows_w=4, t=3, splits=2),  # two workgroups share the channels
+    dict(kernel=3, nt=4, cb=4, waves=8, cg=1, rows_w=4, t=3, splits=2),  # two workgroups share the channels (partial results + reduction)
     dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=3),  # 6 blocks in three parts
     dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=6),  # one block each
 ]
@@ -357,7 +357,7 @@ def test_bias_and_relu_epilogue(oracle, plan):
 
 @pytest.mark.parametrize("splits", [2, 5])
 def test_channel_splits_without_epilogue(oracle, splits):
-    """Partial sums of several workgroups added with atomics: the plain entry point, a strip layout, a ragged batch."""
+    """Partial sums of several workgroups added up by a second launch: the plain entry point, a strip layout, a ragged batch."""
     plan = dict(kernel=3, nt=4, cb=1, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9, splits=splits)
     x, w = rand_case(BIG, 6, 0.2, seed=73)
     _, info = check(BIG, w, x, oracle, plan, what="splits")

@@ -281,3 +281,24 @@ def test_balance_report_counts_streams_and_sees_skew():
     out = B.sconv_balance()
     assert B.lib().sconv_csr_balance(hd.handle, C.byref(out)) == B.ERR["PLAN"]
     assert B.lib().sconv_csr_balance(h.handle, None) == B.ERR["NULL"]
+
+
+def test_fc_planning_and_its_error_paths():
+    """Host side of the fully connected path: which handles and batch sizes it takes, and that the tiling
+    follows the batch (no GPU needed: planning and packing only)."""
+    rng = np.random.default_rng(3)
+    K, Cin = 300, 500
+    w = np.where(rng.random((K, Cin, 1, 1)) < 0.1, rng.standard_normal((K, Cin, 1, 1)), 0).astype(np.float32)
+    h = B.sconv_create_csr(B.fc_layer(Cin, K), w)
+    p256 = B.sconv_fc_plan(h, 256)
+    assert p256["kernel"] == 3 and p256["nt"] == 4 and p256["t"] * p256["cg"] == 1 and p256["band"] == 1
+    p1024 = B.sconv_fc_plan(h, 1024)
+    assert p1024["t"] * p1024["cg"] == 4
+    assert B.sconv_fc_plan(h, 2048)["t"] * B.sconv_fc_plan(h, 2048)["cg"] == 4   # two tiles of 1024
+    L = B.lib()
+    p = B.sconv_plan()
+    for n in (0, 2, 6, 1028):   # not a multiple of 4; two tiles of 514 images, not a multiple of 4
+        assert L.sconv_fc_plan(h.handle, n, C.byref(p)) == B.ERR["BATCH"], n
+    assert L.sconv_fc_plan(h.handle, 256, None) == B.ERR["NULL"]
+    conv = B.sconv_create_csr(wl.LAYERS["conv3"], np.zeros((384, 256, 3, 3), dtype=np.float32))
+    assert L.sconv_fc_plan(conv.handle, 256, C.byref(p)) == B.ERR["DESC"]
