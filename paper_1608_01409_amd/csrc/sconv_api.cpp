@@ -396,18 +396,33 @@ static int plan_fc(sconv_csr *h, int N)
     const int tiles = (N + 1023) / 1024;
     if (N % (4 * tiles)) return SCONV_ERR_BATCH;
     const int nc = N / tiles;
+    // f consecutive features form one channel of f rows (a filter of f x 1 taps, one output row): the same
+    // arithmetic, but a channel plane is f times larger, so that every wave of a workgroup has a part of
+    // it to stage when the batch alone gives a plane of only a few hundred floats
+    int f = 1;
+    if (tiles == 1)
+        for (int c : {16, 8, 4, 2})
+            if (h->desc.C % c == 0 && c * nc <= 1024) {
+                f = c;
+                break;
+            }
     sconv_desc kd = h->desc;
+    kd.C = h->desc.C / f;
+    kd.H = f;
+    kd.R = f;
     kd.W = nc / 4;
     Canonical kc;
     kc.rowptr = h->canon.rowptr;
     kc.colidx = h->canon.colidx;
     kc.val = h->canon.val;
     kc.off.resize(h->canon.off.size());
-    for (size_t j = 0; j < kc.off.size(); ++j) kc.off[j] = h->canon.off[j] * kd.W; // feature c = plane c of the wide image
-    sconv_plan req;
-    std::memset(&req, 0, sizeof(req));
+    for (size_t j = 0; j < kc.off.size(); ++j) kc.off[j] = h->canon.off[j] * kd.W; // feature c = row c of the wide image
+    // fields of the plan the handle was created with are honoured where they apply to this mapping
+    sconv_plan req = h->requested;
     req.kernel = 3;
     req.nt = 4;
+    req.band = 0;
+    req.strip = 0;
     const double avg = kd.K ? (double)kc.val.size() / kd.K : 0.0;
     LdsTiling t;
     int rc = make_lds_tiling(kd, req, 4 * tiles, avg, t);
@@ -463,7 +478,7 @@ extern "C" int sconv_fc_forward(sconv_csr *h, const float *in_t, float *out_t, i
     const LdsTiling &t = h->fc_flat.t;
     const int64_t C = h->desc.C, K = h->desc.K, nc = N / h->fc_tiles;
     Lds2Layout lay;
-    lay.in_tile = nc; lay.in_img = 1; lay.in_ch = N; lay.in_pos = 4;
+    lay.in_tile = nc; lay.in_img = 1; lay.in_ch = (int64_t)h->fc_desc.H * N; lay.in_pos = 4;
     lay.in_rec_fixed = C * N * 4; lay.in_rec_img = 0; lay.in_rec_tile = nc * 4;
     lay.out_tile = nc; lay.out_band = 0; lay.out_row = N; lay.out_img = 1; lay.out_pos = 4;
     Epilogue ep;
