@@ -26,13 +26,20 @@ from . import binding as B
 from . import workloads as wl
 
 
-def time_gpu(fn, iters: int, warm: int = 3) -> float:
-    """Mean milliseconds per call, HIP events on the current stream, back-to-back launches."""
-    for _ in range(warm):
-        fn()
+def time_gpu(fn, iters: int, warm: int = 3, warm_ms: float = 30.0) -> float:
+    """Mean milliseconds per call, HIP events on the current stream, back-to-back launches.  The warm-up
+    runs for at least warm_ms of GPU time: after the host-side packing of a new handle the GPU has dropped
+    to a low clock state and the first milliseconds of work run well below the sustained rate."""
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(warm):
+        fn()
+    e1.record()
     torch.cuda.synchronize()
+    per_call = max(e0.elapsed_time(e1) / warm, 1e-3)
+    for _ in range(int(warm_ms / per_call) + 1):   # no synchronisation between the warm-up and the timed calls
+        fn()
     e0.record()
     for _ in range(iters):
         fn()
