@@ -312,16 +312,18 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     // a tiling the library chose itself follows the batch size (only when none of its fields was requested)
     const sconv_plan &rq = h->requested;
     const bool free_choice = !rq.nt && !rq.cb && !rq.waves && !rq.cg && !rq.rows_w && !rq.t && !rq.band && !rq.strip && !rq.splits;
-    if (use_lds && free_choice && N >= 4 && N != h->planned_n) {
+    // (batches below 4 use the tiling of batch 4: one tile of 4 images, not all of them present)
+    const int n_plan = N < 4 ? 4 : N;
+    if (use_lds && free_choice && n_plan != h->planned_n) {
         try {
-            const int prc = plan_lds(h, N);
+            const int prc = plan_lds(h, n_plan);
             if (prc) return prc;
         } catch (const std::bad_alloc &) {
             return SCONV_ERR_NOMEM;
         }
     }
-    const LdsTiling &til = h->flat ? h->lds_flat.t : h->lds.t;
-    if (use_lds && h->requested.kernel == 0 && N < 4 && til.p.nt >= 4) use_lds = false;
+    // the per-row-stream kernel's tiles of 4 images and more are no match for the direct kernel on 1-3 images
+    if (use_lds && !h->flat && h->requested.kernel == 0 && N < 4 && h->lds.t.p.nt >= 4) use_lds = false;
     int rc;
     if (use_lds && h->phased) {
         // re-order the input into phase images (scratch owned by the handle, grown on demand)
