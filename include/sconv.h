@@ -109,7 +109,8 @@ int sconv_csr_export(const sconv_csr *h, int32_t *rowptr, int32_t *off, float *v
  * Undo the kernel packing: walks the packed (reordered, channel-blocked,
  * byte-offset) arrays the kernels read and rebuilds canonical lowered CSR from
  * them alone.  `which` = 1 for the LDS-tiled kernel's arrays (SCONV_ERR_PLAN if
- * the handle has none), 2 for the direct kernel's.  Same conventions as
+ * the handle has none), 2 for the direct kernel's, 3 for the arrays
+ * sconv_fc_forward last packed (SCONV_ERR_PLAN before its first plan).  Same conventions as
  * sconv_csr_export.  Equality of the two exports shows the packing loses and
  * invents nothing.
  */

@@ -276,6 +276,17 @@ extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowp
             }
         } else if (which == 2) {
             rc = unpack_direct(h->desc, h->direct, c);
+        } else if (which == 3) {
+            // the fully connected packing: offsets are feature * (positions per tile) in the wide image
+            if (h->fc_n <= 0) return SCONV_ERR_PLAN;
+            rc = unpack_flat(h->fc_desc, h->fc_flat, c);
+            if (!rc) {
+                const int w = h->fc_desc.W;
+                for (auto &o : c.off) {
+                    if (o % w) return SCONV_ERR_CSR;
+                    o /= w;
+                }
+            }
         } else {
             return SCONV_ERR_PLAN;
         }

@@ -295,6 +295,13 @@ def test_fc_planning_and_its_error_paths():
     p1024 = B.sconv_fc_plan(h, 1024)
     assert p1024["t"] * p1024["cg"] == 4
     assert B.sconv_fc_plan(h, 2048)["t"] * B.sconv_fc_plan(h, 2048)["cg"] == 4   # two tiles of 1024
+    # every packing unpacks to the canonical arrays, bit for bit
+    er, eo, ev = B.sconv_csr_export(h)
+    for n in (2048, 256, 64, 8):
+        B.sconv_fc_plan(h, n)
+        r, o, v = B.sconv_csr_unpack(h, 3)
+        assert np.array_equal(r, er) and np.array_equal(o, eo) and np.array_equal(v.view(np.uint32), ev.view(np.uint32)), n
+    assert np.array_equal(eo, np.nonzero(w.reshape(K, Cin))[1])   # the lowered offset of a 1x1 layer on a 1x1 image is the feature
     L = B.lib()
     p = B.sconv_plan()
     for n in (0, 2, 6, 1028):   # not a multiple of 4; two tiles of 514 images, not a multiple of 4
