@@ -309,3 +309,31 @@ def test_fc_planning_and_its_error_paths():
     assert L.sconv_fc_plan(h.handle, 256, None) == B.ERR["NULL"]
     conv = B.sconv_create_csr(wl.LAYERS["conv3"], np.zeros((384, 256, 3, 3), dtype=np.float32))
     assert L.sconv_fc_plan(conv.handle, 256, C.byref(p)) == B.ERR["DESC"]
+
+
+def test_size_limits_are_refused_not_wrapped():
+    """Maximum sizes: descriptions whose lowered offsets or CSR columns would leave int32 are refused with
+    SCONV_ERR_RANGE; the largest ones below the limits are accepted (an empty pattern, so nothing is big)."""
+    L = B.lib()
+
+    def create_empty(**kw):
+        layer = wl.small_layer("lim", **kw)
+        d = B.make_desc(layer)
+        rowptr = np.zeros(layer.K + 1, dtype=np.int32)
+        out = C.c_void_p()
+        rc = L.sconv_create_csr_from_arrays(C.byref(d), rowptr.ctypes.data_as(C.c_void_p), None, None, None, C.byref(out))
+        if rc == B.SCONV_OK:
+            L.sconv_destroy_csr(out)
+        return rc
+
+    # C * Hp * Wp must stay below 2^30
+    assert create_empty(C=1024, H=1024, W=1024, K=1, R=1, S=1, stride=1, pad=0, groups=1) == B.ERR["RANGE"]
+    assert create_empty(C=1023, H=1024, W=1024, K=1, R=1, S=1, stride=1, pad=0, groups=1) == B.SCONV_OK
+    assert create_empty(C=1021, H=1024, W=1024, K=1, R=3, S=3, stride=1, pad=1, groups=1) == B.ERR["RANGE"]  # 1021 * 1026^2: the padding counts
+    assert create_empty(C=1020, H=1024, W=1024, K=1, R=3, S=3, stride=1, pad=1, groups=1) == B.SCONV_OK
+    # filter extents and padding are stored in 8 bits by the direct kernel's packing
+    assert create_empty(C=1, H=300, W=300, K=1, R=256, S=1, stride=1, pad=0, groups=1) == B.ERR["RANGE"]
+    assert create_empty(C=1, H=300, W=300, K=1, R=255, S=255, stride=1, pad=0, groups=1) == B.SCONV_OK
+    assert create_empty(C=1, H=8, W=8, K=1, R=3, S=3, stride=1, pad=256, groups=1) == B.ERR["RANGE"]
+    # K * Cg * R * S (the dense weight count) below 2^31
+    assert create_empty(C=4096, H=16, W=16, K=65536, R=3, S=3, stride=1, pad=1, groups=1) == B.ERR["RANGE"]
