@@ -105,18 +105,27 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
             emit(f"s_cbranch_scc1 {end}")
             emit(f"v_cmp_ne_u32_e32 vcc, -1, {OP['voff%d' % j]}")
             emit("s_mov_b64 exec, vcc")
-            emit(f"s_mov_b32 s{SD}, s{STMP}")
+            # two channels per trip; M0 (the LDS destination) and the scalar source offset advance in place.
+            # An instruction always separates a write of M0 from the load that uses it.
+            emit(f"s_mov_b32 m0, s{STMP}")
             emit(f"s_mov_b32 s{SS}, s{SSOFF}")
-            emit(f"s_mov_b32 vcc_lo, s{SNCH}")       # vcc is free again: channel counter
-            lp = label("stj")
+            emit(f"s_lshr_b32 vcc_lo, s{SNCH}, 1")       # vcc is free again: pairs of channels to go
+            lp, tail, nxt = label("stj"), label("sttail"), label("stnext")
+            emit("s_cmp_eq_u32 vcc_lo, 0")
+            emit(f"s_cbranch_scc1 {tail}")
             emit(f"{lp}:")
-            emit(f"s_mov_b32 m0, s{SD}")
-            emit(f"s_add_u32 s{SD}, s{SD}, s{SPLANE}")
-            emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
-            emit(f"s_add_u32 s{SS}, s{SS}, s{SHW4}")
+            for _ in range(2):
+                emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
+                emit(f"s_add_u32 m0, m0, s{SPLANE}")
+                emit(f"s_add_u32 s{SS}, s{SS}, s{SHW4}")
             emit("s_sub_u32 vcc_lo, vcc_lo, 1")
             emit("s_cmp_lg_u32 vcc_lo, 0")
             emit(f"s_cbranch_scc1 {lp}")
+            emit(f"{tail}:")
+            emit(f"s_bitcmp1_b32 s{SNCH}, 0")
+            emit(f"s_cbranch_scc0 {nxt}")
+            emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
+            emit(f"{nxt}:")
             emit(f"s_add_u32 s{STMP}, s{STMP}, {OP['slabstep']}")
         emit(f"{end}:")
         emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
