@@ -35,8 +35,8 @@ def main() -> int:
                          "scaling the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (batch-sharded data parallelism needs no "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path shards over the batch with no exchange "
+              "between GPUs, so more GPUs add nothing to measure); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
