@@ -91,14 +91,16 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Row pitch of the LDS plane.  W + pad columns are enough for the reads: one that runs into the right
 // padding of a row (X >= W + pad) lands on column X - pitch < pad of the next row, left padding, zero as
-// well.  The pitch must also hold a whole output row, which is wider than that when pad > S - 1.
+// well.  The pitch must also hold a whole output row, which is wider than that when pad > S - 1, and a
+// whole filter row, so that two taps never share a cell (images narrower than the filter: both taps would
+// read nothing but padding, yet the packing could no longer be decoded).
 // With strips, lane l of a chunk sits on cell (l / strip) * pitch + l % strip; a pitch congruent to the strip
 // width modulo 16 makes that congruent to l, so that the 64 lanes of a 16-byte read fall on the LDS banks
 // exactly as 64 consecutive cells do (the natural pitch costs a third of the read rate in bank conflicts).
 static int lds_pitch(const sconv_desc &d, int strip = 0)
 {
     const Geometry g = geometry(d);
-    int pitch = std::max(d.W + d.pad, g.OW);
+    int pitch = std::max(std::max(d.W + d.pad, g.OW), d.S);
     while (strip && (pitch - strip) % 16) ++pitch;
     return pitch;
 }

@@ -337,3 +337,41 @@ def test_size_limits_are_refused_not_wrapped():
     assert create_empty(C=1, H=8, W=8, K=1, R=3, S=3, stride=1, pad=256, groups=1) == B.ERR["RANGE"]
     # K * Cg * R * S (the dense weight count) below 2^31
     assert create_empty(C=4096, H=16, W=16, K=65536, R=3, S=3, stride=1, pad=1, groups=1) == B.ERR["RANGE"]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_layers_pack_and_unpack_bit_exactly(oracle, seed):
+    """Seeded random layers (strides, pads, groups, odd sizes) and densities: the library's canonical arrays
+    equal the oracle's, and whatever packing the library chooses unpacks to them again; the same for the
+    fully connected packing at a few batch sizes."""
+    rng = np.random.default_rng(9000 + seed)
+    groups = int(rng.choice([1, 1, 2, 3]))
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    stride, pad = int(rng.choice([1, 1, 2, 3])), int(rng.integers(0, 3))
+    H = max(int(rng.integers(1, 40)), R - 2 * pad, 1)
+    W = max(int(rng.integers(1, 40)), S - 2 * pad, 1)
+    layer = wl.small_layer("rnd", C=groups * int(rng.integers(1, 12)), H=H, W=W, K=groups * int(rng.integers(1, 30)),
+                           R=R, S=S, stride=stride, pad=pad, groups=groups)
+    dens = float(rng.choice([0.02, 0.1, 0.5, 1.0]))
+    w = np.where(rng.random((layer.K, layer.Cg, R, S)) < dens, rng.standard_normal((layer.K, layer.Cg, R, S)), 0).astype(np.float32)
+    o_rowptr, o_col, o_val = oracle.csr_from_dense(layer, w)
+    o_off = oracle.lower_offsets(layer, o_rowptr, o_col)
+    h = B.sconv_create_csr(layer, w)
+    r, o, v = B.sconv_csr_export(h)
+    assert np.array_equal(r, o_rowptr) and np.array_equal(o, o_off) and np.array_equal(v.view(np.uint32), o_val.view(np.uint32))
+    for which in (1, 2):
+        try:
+            r2, o2, v2 = B.sconv_csr_unpack(h, which)
+        except B.SconvError as e:   # a layer the LDS kernels cannot take has only the direct packing
+            assert which == 1 and e.status == B.ERR["PLAN"]
+            continue
+        assert np.array_equal(r2, o_rowptr) and np.array_equal(o2, o_off), (which, layer)
+        assert np.array_equal(v2.view(np.uint32), o_val.view(np.uint32))
+    K, Cin = int(rng.integers(1, 70)), int(rng.integers(1, 90))
+    wf = np.where(rng.random((K, Cin, 1, 1)) < dens, rng.standard_normal((K, Cin, 1, 1)), 0).astype(np.float32)
+    hf = B.sconv_create_csr(B.fc_layer(Cin, K), wf)
+    er, eo, ev = B.sconv_csr_export(hf)
+    for n in (4, 64, 520, 2048):
+        B.sconv_fc_plan(hf, n)
+        r3, o3, v3 = B.sconv_csr_unpack(hf, 3)
+        assert np.array_equal(r3, er) and np.array_equal(o3, eo) and np.array_equal(v3.view(np.uint32), ev.view(np.uint32)), n
