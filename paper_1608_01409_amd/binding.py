@@ -124,13 +124,14 @@ class Csr:
     def __init__(self, handle, layer):
         self._h = C.c_void_p(handle)
         self.layer = layer
+        self._destroy = lib().sconv_destroy_csr   # module globals may be gone when __del__ runs at exit
 
     def __del__(self):
         self.destroy()
 
     def destroy(self):
         if getattr(self, "_h", None):
-            lib().sconv_destroy_csr(self._h)
+            self._destroy(self._h)
             self._h = None
 
     @property
