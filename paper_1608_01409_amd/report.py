@@ -181,11 +181,18 @@ def report_fc(iters):
         nnz = int(np.count_nonzero(w))
         flops = 2.0 * nnz * N
         plan = B.sconv_fc_plan(h, N)
+        # Section 2.2's model on the layer as a 1x1 convolution of 1x1 images, with the measured dense rate
+        m = B.sconv_machine_gfx950()
+        m.dense_flops = 2.0 * K * C_in * N / (ms_dense * 1e-3)
+        pred = B.sconv_model_predict(B.fc_layer(C_in, K), N, nnz / w.size, None, m)
         row = dict(report="fc", layer=name, N=N, density=dens, nnz=nnz, t_us=ms * 1e3, tflops=flops / ms / 1e9,
                    t_dense_us=ms_dense * 1e3, dense_tflops=2.0 * K * C_in * N / ms_dense / 1e9, speedup=ms_dense / ms,
-                   weight_gb_per_s=8.0 * nnz / (ms * 1e-3) / 1e9, plan=plan)
+                   weight_gb_per_s=8.0 * nnz / (ms * 1e-3) / 1e9, t_model_us=pred["t_sparse"] * 1e6,
+                   model_bandwidth_bound=bool(pred["bandwidth_bound"]), model_x_upper=pred["x_upper"],
+                   model_x_lower=pred["x_lower"], plan=plan)
         print(f"{name}: N {N} x {dens} nnz {nnz}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s, dense fp32 matmul {ms_dense*1e3:.1f} us "
-              f"({row['dense_tflops']:.1f} TFLOP/s), speedup {ms_dense/ms:.2f}, plan {plan}")
+              f"({row['dense_tflops']:.1f} TFLOP/s), speedup {ms_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us "
+              f"({'bandwidth' if pred['bandwidth_bound'] else 'compute'} bound, useful x in ({pred['x_upper']:.3f}, {pred['x_lower']:.3f})), plan {plan}")
         emit(row)
 
 
