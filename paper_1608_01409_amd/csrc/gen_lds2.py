@@ -49,7 +49,7 @@ SA, SB, SN = 36, 52, 68
 SPTR, SCNT, STMP = 84, 86, 87
 SBLK, SNBLK, SSEG = 88, 89, 90
 SBUF, SSTRIDE, SPLANE, SHW4 = 92, 93, 94, 95
-SD, SS, SNCH, STGT = 96, 97, 98, 99              # staging temporaries
+SOFF, SS, SNCH, STGT = 96, 97, 98, 99            # stream byte offset; staging temporaries
 SNXT = 31                                        # chunks in the next block's segment
 SX0, SX1 = SSEG, SSEG + 1                        # store address pair: the segment pointer is done by then
 MAX_VGPR = 128
@@ -137,9 +137,8 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         """One chunk: multiply the 8 entries of A; reads of the entries D ahead (A's tail, B's head) are issued."""
         def entry_w1(p):
             return w1(A, p) if p < CH else w1(B, p - CH)
-        emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], 0x0")
-        emit(f"s_add_u32 s{SPTR}, s{SPTR}, {hex(4 * W)}")
-        emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
+        emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
+        emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
         if batch:
             for j in range(CH):
                 emit(f"v_mad_u32_u16 v{VA0 + j}, {entry_w1(j + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
@@ -159,8 +158,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         if batch:
             emit("s_set_gpr_idx_off")
         emit("s_waitcnt lgkmcnt(0)")
-        emit(f"s_sub_u32 s{SCNT}, s{SCNT}, 1")
-        emit(f"s_cmp_lg_u32 s{SCNT}, 0")
+        emit(f"s_cmp_lg_u32 s{SOFF}, s{SCNT}")          # SCNT: the offset at which this segment's loads end
 
     # ------------------------------------------------------------------ set-up
     emit(f"s_mov_b64 s[{SEXEC}:{SEXEC + 1}], exec")
@@ -187,25 +185,26 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     # The segments of one wave slot follow each other in memory, block after block, so the two chunks the
     # loop has read ahead when a segment ends are the first two of the next one: only block 0 loads them here.
     emit("s_waitcnt lgkmcnt(0)")
-    emit(f"s_add_u32 s{SPTR}, s{SN + 2}, s{SN}")
-    emit(f"s_addc_u32 s{SPTR + 1}, s{SN + 3}, 0")
+    emit(f"s_mov_b64 s[{SPTR}:{SPTR + 1}], s[{SN + 2}:{SN + 3}]")      # base of the streams; SOFF runs over them
+    emit(f"s_mov_b32 s{SOFF}, s{SN}")
     emit(f"s_mov_b32 s{SNXT}, s{SN + 1}")
-    emit(f"s_load_dwordx16 s[{SA}:{SA + W - 1}], s[{SPTR}:{SPTR + 1}], 0x0")
-    emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], {hex(4 * W)}")
-    emit(f"s_add_u32 s{SPTR}, s{SPTR}, {hex(8 * W)}")
-    emit(f"s_addc_u32 s{SPTR + 1}, s{SPTR + 1}, 0")
+    emit(f"s_load_dwordx16 s[{SA}:{SA + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
+    emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
+    emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
+    emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
 
     # ------------------------------------------------------------------ channel blocks
     blk, nostage, segdone, noreads = label("blk"), label("nostage"), label("segdone"), label("noreads")
     emit(f"{blk}:")
     emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
     emit("s_barrier")
-    emit(f"s_mov_b32 s{SCNT}, s{SNXT}")
+    emit(f"s_lshl_b32 s{SCNT}, s{SNXT}, 6")                # this block's chunks -> where its loads end
+    emit(f"s_add_u32 s{SCNT}, s{SCNT}, s{SOFF}")
     emit(f"s_load_dword s{SNXT}, s[{SSEG}:{SSEG + 1}], 0x4")   # chunks of the next block (one spare entry ends the table)
     emit(f"s_add_u32 s{SSEG}, s{SSEG}, 8")
     emit(f"s_addc_u32 s{SSEG + 1}, s{SSEG + 1}, 0")
     # first reads of this block's stream go out before the loads of the next block are issued
-    emit(f"s_cmp_eq_u32 s{SCNT}, 0")
+    emit(f"s_cmp_eq_u32 s{SCNT}, s{SOFF}")                 # no chunks in this block
     emit(f"s_cbranch_scc1 {noreads}")
     emit(f"s_add_u32 s{STMP}, s{SBUF}, {OP['ldsbase']}")
     emit(f"v_add_u32 v{VLB}, s{STMP}, {OP['lane_byte']}")
@@ -221,7 +220,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
     stage(STGT)
     emit(f"{nostage}:")
-    emit(f"s_cmp_eq_u32 s{SCNT}, 0")
+    emit(f"s_cmp_eq_u32 s{SCNT}, s{SOFF}")
     emit(f"s_cbranch_scc1 {segdone}")
     loop, exit1, exit2 = label("chunk"), label("exita"), label("exitb")
     emit(f"{loop}:")
