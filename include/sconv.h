@@ -121,7 +121,12 @@ int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t
  * contiguous fp32; `in` is NOT padded (padding is applied on chip).  `out` is
  * overwritten, rows without nonzeros with zeros.  Enqueued on `hip_stream`
  * (a hipStream_t; NULL = the default stream) of the current device and not
- * waited for.  `in` and `out` must not overlap.
+ * waited for.  `in` and `out` must not overlap.  A tiling the library chose
+ * itself follows N: the first call with a new batch size chooses and packs for
+ * it (host work, milliseconds, and an upload); the packings of the last four
+ * tilings stay on the device, so alternating batch sizes cost nothing more.
+ * Calls on one handle must not overlap in time (the handle owns scratch);
+ * different handles are independent.
  */
 int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream);
 

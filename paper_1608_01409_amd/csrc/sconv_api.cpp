@@ -2,11 +2,37 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <map>
 #include <new>
+#include <utility>
+#include <vector>
 
 #include "sconv_internal.h"
 
 using namespace sconv;
+
+// An earlier packing of a handle, kept with its device copies: a caller that alternates between batch sizes
+// gets it back instead of packing and uploading again.
+struct StashedPacking {
+    bool flat = false;
+    PackedLds lds;
+    PackedFlat lds_flat;
+    DeviceLds dev;
+    bool uploaded = false;
+    // fully connected packings only
+    int fc_n = 0, fc_tiles = 0;
+    sconv_desc fc_desc;
+};
+static const size_t kStashed = 3; // packings kept besides the current one
+
+static void release_arrays(DeviceLds &dev)
+{
+    release(dev.pairs);
+    release(dev.seg_ptr);
+    release(dev.row_of);
+    release(dev.store_tbl);
+    dev = DeviceLds();
+}
 
 struct sconv_csr {
     sconv_desc desc;
@@ -21,6 +47,8 @@ struct sconv_csr {
     DeviceDirect dev_direct;
     bool lds_uploaded = false, direct_uploaded = false;
     int planned_n = 0;       // batch size the current LDS tiling was chosen for
+    std::map<int, sconv_plan> plan_of_n;     // tilings already chosen, by batch size
+    std::vector<StashedPacking> stash;       // earlier packings, oldest first
     // the layer the LDS kernels run: the layer itself, or for stride > 1 its stride-1 form over phase images
     bool phased = false;
     sconv_desc kdesc;
@@ -37,6 +65,7 @@ struct sconv_csr {
     PackedFlat fc_flat;
     DeviceLds fc_dev;
     bool fc_uploaded = false;
+    std::vector<StashedPacking> fc_stash;
     int hip_err = 0;
 };
 
@@ -82,19 +111,45 @@ static int plan_lds(sconv_csr *h, int n)
     const sconv_desc &d = h->kdesc;
     const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
     LdsTiling t;
-    int rc = make_lds_tiling(d, h->requested, n, avg, t);
+    int rc;
+    auto known = h->plan_of_n.find(n);
+    if (known != h->plan_of_n.end()) {
+        rc = make_lds_tiling(d, known->second, n, avg, t); // every field given: no search
+    } else {
+        rc = make_lds_tiling(d, h->requested, n, avg, t);
+        if (!rc) h->plan_of_n[n] = t.p;
+    }
     if (rc) return rc;
     h->planned_n = n;
     if (h->has_lds && same_plan(t.p, h->flat ? h->lds_flat.t.p : h->lds.t.p)) return SCONV_OK;
-    if (h->lds_uploaded) { // hipFree waits for launches that still read the old arrays
-        release(h->dev_lds.pairs);
-        release(h->dev_lds.seg_ptr);
-        release(h->dev_lds.row_of);
-        release(h->dev_lds.store_tbl);
+    if (h->has_lds) { // set the current packing aside, device copies and all
+        StashedPacking old;
+        old.flat = h->flat;
+        old.lds = std::move(h->lds);
+        old.lds_flat = std::move(h->lds_flat);
+        old.dev = h->dev_lds;
+        old.uploaded = h->lds_uploaded;
+        h->stash.push_back(std::move(old));
         h->dev_lds = DeviceLds();
         h->lds_uploaded = false;
+        h->has_lds = false;
+        while (h->stash.size() > kStashed) { // hipFree waits for launches that still read the arrays
+            release_arrays(h->stash.front().dev);
+            h->stash.erase(h->stash.begin());
+        }
     }
-    h->has_lds = false;
+    for (size_t i = 0; i < h->stash.size(); ++i) {
+        StashedPacking &sp = h->stash[i];
+        if (!same_plan(t.p, sp.flat ? sp.lds_flat.t.p : sp.lds.t.p)) continue;
+        h->flat = sp.flat;
+        h->lds = std::move(sp.lds);
+        h->lds_flat = std::move(sp.lds_flat);
+        h->dev_lds = sp.dev;
+        h->lds_uploaded = sp.uploaded;
+        h->has_lds = true;
+        h->stash.erase(h->stash.begin() + (long)i);
+        return SCONV_OK;
+    }
     h->flat = t.p.kernel == 3;
     rc = h->flat ? pack_flat(d, h->kc(), t, h->lds_flat) : pack_lds(d, h->kc(), t, h->lds);
     if (rc) return rc;
@@ -408,6 +463,36 @@ static int plan_fc(sconv_csr *h, int N)
     // one wave covers at most 4 x 256 images; larger batches are cut into equal tiles
     const int tiles = (N + 1023) / 1024;
     if (N % (4 * tiles)) return SCONV_ERR_BATCH;
+    if (h->fc_n > 0) { // set the current packing aside; one for this batch size may be waiting there
+        StashedPacking old;
+        old.flat = true;
+        old.lds_flat = std::move(h->fc_flat);
+        old.dev = h->fc_dev;
+        old.uploaded = h->fc_uploaded;
+        old.fc_n = h->fc_n;
+        old.fc_tiles = h->fc_tiles;
+        old.fc_desc = h->fc_desc;
+        h->fc_stash.push_back(std::move(old));
+        h->fc_dev = DeviceLds();
+        h->fc_uploaded = false;
+        h->fc_n = 0;
+        while (h->fc_stash.size() > kStashed) {
+            release_arrays(h->fc_stash.front().dev);
+            h->fc_stash.erase(h->fc_stash.begin());
+        }
+    }
+    for (size_t i = 0; i < h->fc_stash.size(); ++i) {
+        StashedPacking &sp = h->fc_stash[i];
+        if (sp.fc_n != N) continue;
+        h->fc_flat = std::move(sp.lds_flat);
+        h->fc_dev = sp.dev;
+        h->fc_uploaded = sp.uploaded;
+        h->fc_tiles = sp.fc_tiles;
+        h->fc_desc = sp.fc_desc;
+        h->fc_n = N;
+        h->fc_stash.erase(h->fc_stash.begin() + (long)i);
+        return SCONV_OK;
+    }
     const int nc = N / tiles;
     // f consecutive features form one channel of f rows (a filter of f x 1 taps, one output row): the same
     // arithmetic, but a channel plane is f times larger, so that every wave of a workgroup has a part of
@@ -441,8 +526,6 @@ static int plan_fc(sconv_csr *h, int N)
     int rc = make_lds_tiling(kd, req, 4 * tiles, avg, t);
     if (rc) return rc;
     t.out_pos = 4; // the four images of a cell are consecutive in the output row
-    if (h->fc_uploaded) release_fc(h);
-    h->fc_n = 0;
     rc = pack_flat(kd, kc, t, h->fc_flat);
     if (rc) return rc;
     h->fc_desc = kd;
@@ -512,6 +595,8 @@ extern "C" void sconv_destroy_csr(sconv_csr *h)
     release(h->phase_buf);
     release(h->part_buf);
     release_fc(h);
+    for (auto &sp : h->stash) release_arrays(sp.dev);
+    for (auto &sp : h->fc_stash) release_arrays(sp.dev);
     release(h->dev_direct.rowptr);
     release(h->dev_direct.trip);
     delete h;

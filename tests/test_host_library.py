@@ -297,8 +297,10 @@ def test_fc_planning_and_its_error_paths():
     assert B.sconv_fc_plan(h, 2048)["t"] * B.sconv_fc_plan(h, 2048)["cg"] == 4   # two tiles of 1024
     # every packing unpacks to the canonical arrays, bit for bit
     er, eo, ev = B.sconv_csr_export(h)
-    for n in (2048, 256, 64, 8):
-        B.sconv_fc_plan(h, n)
+    plans = {}
+    for n in (2048, 256, 64, 8, 256, 2048, 12, 16, 20, 256, 8):   # earlier packings come back, the oldest are dropped
+        p_n = B.sconv_fc_plan(h, n)
+        assert plans.setdefault(n, p_n) == p_n
         r, o, v = B.sconv_csr_unpack(h, 3)
         assert np.array_equal(r, er) and np.array_equal(o, eo) and np.array_equal(v.view(np.uint32), ev.view(np.uint32)), n
     assert np.array_equal(eo, np.nonzero(w.reshape(K, Cin))[1])   # the lowered offset of a 1x1 layer on a 1x1 image is the feature
