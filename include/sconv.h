@@ -227,7 +227,8 @@ int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const
  * How evenly the packing spreads the nonzeros (the load-balance step of the
  * path; the paper only asks that all cores be used, Section 3).  The waves of a
  * workgroup meet at a barrier after every channel block, so a block costs what
- * its longest wave stream costs.  All counts are in stream chunks of 8 entries.
+ * its longest wave stream costs.  All counts are in stream chunks of 8 entries
+ * (a segment may open with a half chunk of 4).
  * Only for handles packed for kernel 3 (SCONV_ERR_PLAN otherwise).
  */
 typedef struct {

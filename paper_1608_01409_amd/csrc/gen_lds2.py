@@ -47,7 +47,7 @@ SCB, SREM, SSOFF = 28, 29, 30
 SEXEC = 34
 SA, SB, SN = 36, 52, 68
 SPTR, SCNT, STMP = 84, 86, 87
-SBLK, SNBLK, SSEG = 88, 89, 90
+SHALF, SLEFT, SSEG = 88, 89, 90                  # first chunk of the block is a half chunk; blocks left
 SBUF, SSTRIDE, SPLANE, SHW4 = 92, 93, 94, 95
 SOFF, SS, SNCH, STGT = 96, 97, 98, 99            # stream byte offset; staging temporaries
 SNXT = 31                                        # chunks in the next block's segment
@@ -133,16 +133,17 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{STMP}")
         emit(f"s_sub_u32 s{SREM}, s{SREM}, s{SNCH}")
 
-    def body(A, B, N):
-        """One chunk: multiply the 8 entries of A; reads of the entries D ahead (A's tail, B's head) are issued."""
+    def body(A, B, N, n=CH):
+        """One chunk: multiply the first n entries of A (8, or 4 for the half chunk that may open a segment);
+        reads of the entries D ahead (A's tail, B's head) are issued."""
         def entry_w1(p):
-            return w1(A, p) if p < CH else w1(B, p - CH)
+            return w1(A, p) if p < n else w1(B, p - n)
         emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
         emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
         if batch:
-            for j in range(CH):
+            for j in range(n):
                 emit(f"v_mad_u32_u16 v{VA0 + j}, {entry_w1(j + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
-        for u in range(CH):
+        for u in range(n):
             slot = u % D
             va = VA0 + (u if batch else slot)
             if not batch:
@@ -167,13 +168,12 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_load_dwordx8 s[{SN}:{SN + 7}], {OP['kern']}, {hex(OFF_CONSTS)}")
     emit("s_waitcnt lgkmcnt(0)")
     emit(f"s_mov_b32 s{SCB}, s{SN}")
-    emit(f"s_mov_b32 s{SNBLK}, {OP['nblk']}")      # blocks and channels of this workgroup's channel range
+    emit(f"s_mov_b32 s{SLEFT}, {OP['nblk']}")      # blocks and channels of this workgroup's channel range
     emit(f"s_mov_b32 s{SREM}, {OP['nch']}")
     emit(f"s_mov_b32 s{SPLANE}, s{SN + 3}")
     emit(f"s_mov_b32 s{SSTRIDE}, s{SN + 4}")
     emit(f"s_mov_b32 s{SHW4}, s{SN + 5}")
     emit(f"s_mov_b32 s{SSOFF}, {OP['soff0']}")
-    emit(f"s_mov_b32 s{SBLK}, 0")
     emit(f"s_mov_b64 s[{SSEG}:{SSEG + 1}], {OP['segp']}")
     emit(f"s_mov_b32 s{SBUF}, 0")
     emit(f"s_load_dwordx2 s[{SN}:{SN + 1}], s[{SSEG}:{SSEG + 1}], 0x0")          # segment of block 0
@@ -198,6 +198,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"{blk}:")
     emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
     emit("s_barrier")
+    emit(f"s_lshr_b32 s{SHALF}, s{SNXT}, 31")              # bit 31: the segment opens with a half chunk
     emit(f"s_lshl_b32 s{SCNT}, s{SNXT}, 6")                # this block's chunks -> where its loads end
     emit(f"s_add_u32 s{SCNT}, s{SCNT}, s{SOFF}")
     emit(f"s_load_dword s{SNXT}, s[{SSEG}:{SSEG + 1}], 0x4")   # chunks of the next block (one spare entry ends the table)
@@ -213,8 +214,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         for t in range(T):
             emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * step * 16}")
     emit(f"{noreads}:")
-    emit(f"s_add_u32 s{STMP}, s{SBLK}, 1")
-    emit(f"s_cmp_ge_u32 s{STMP}, s{SNBLK}")
+    emit(f"s_cmp_le_u32 s{SLEFT}, 1")                      # the last block stages nothing
     emit(f"s_cbranch_scc1 {nostage}")
     emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
     emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
@@ -222,10 +222,16 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"{nostage}:")
     emit(f"s_cmp_eq_u32 s{SCNT}, s{SOFF}")
     emit(f"s_cbranch_scc1 {segdone}")
-    loop, exit1, exit2 = label("chunk"), label("exita"), label("exitb")
+    loop, exit1, exit2, second, half = label("chunk"), label("exita"), label("exitb"), label("second"), label("half")
+    # A segment whose length is an odd number of half chunks opens with 4 entries in a chunk of their own
+    # (the other 4 are never executed): padding to whole chunks of 8 would cost twice as many idle entries.
+    # Its code sits behind the loop, out of the way.
+    emit(f"s_cmp_lg_u32 s{SHALF}, 0")
+    emit(f"s_cbranch_scc1 {half}")
     emit(f"{loop}:")
     body(SA, SB, SN)
     emit(f"s_cbranch_scc0 {exit1}")
+    emit(f"{second}:")
     body(SB, SN, SA)
     emit(f"s_cbranch_scc0 {exit2}")
     body(SN, SA, SB)
@@ -242,10 +248,15 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         emit(f"s_mov_b64 s[{SB + w}:{SB + w + 1}], s[{SA + w}:{SA + w + 1}]")
     for w in range(0, W, 2):
         emit(f"s_mov_b64 s[{SA + w}:{SA + w + 1}], s[{SN + w}:{SN + w + 1}]")
+    emit(f"s_branch {segdone}")
+    emit(f"{half}:")
+    body(SA, SB, SN, 4)
+    emit(f"s_cbranch_scc0 {exit1}")
+    emit(f"s_branch {second}")
     emit(f"{segdone}:")
     emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
-    emit(f"s_add_u32 s{SBLK}, s{SBLK}, 1")
-    emit(f"s_cmp_lt_u32 s{SBLK}, s{SNBLK}")
+    emit(f"s_sub_u32 s{SLEFT}, s{SLEFT}, 1")
+    emit(f"s_cmp_lg_u32 s{SLEFT}, 0")
     emit(f"s_cbranch_scc1 {blk}")
 
     # ------------------------------------------------------------------ epilogue and stores

@@ -265,8 +265,9 @@ extern "C" int sconv_csr_balance(const sconv_csr *h, sconv_balance *out)
             double sum = 0, mx = 0, simd[4] = {0, 0, 0, 0};
             int on_simd[4] = {0, 0, 0, 0};
             for (int r = 0; r < t.rg; ++r) {
-                const double ch = f.seg[((size_t)(wg * t.rg + r) * t.nblk + b) * 2 + 1];
-                out->stream_entries += (int64_t)ch * SCONV_FLAT_CHUNK;
+                const uint32_t word = f.seg[((size_t)(wg * t.rg + r) * t.nblk + b) * 2 + 1];
+                const double ch = (word & 0x7fffffffu) - ((word >> 31) ? 0.5 : 0.0); // a half chunk counts as half
+                out->stream_entries += (int64_t)(ch * SCONV_FLAT_CHUNK + 0.5);
                 sum += ch;
                 mx = std::max(mx, ch);
                 // the cg waves of a row group run the same stream; wave index = r * cg + column group

@@ -245,7 +245,7 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     const int by_lds = std::max(1, (160 * 1024) / (t.lds_bytes + 512));
     const int wpc = std::max(1, std::min(by_lds, 16 / t.p.waves));
     const double rows_wave = (double)g.Kg / (t.nkt * t.rg);
-    const double entries = rows_wave * avg_row_nnz / splits + 3.5 * blocks;
+    const double entries = rows_wave * avg_row_nnz / splits + 1.5 * blocks; // segments are padded to fours
     const double cu_wgs = std::ceil(wgs / 256.0);             // workgroups one CU has to run ...
     const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
     const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
@@ -524,12 +524,25 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
         for (int b = 0; b < t.nblk; ++b) {
             // entries in ascending LDS offset: rows that share a column sit next to each other
             std::stable_sort(bucket[b].begin(), bucket[b].end(), [](uint64_t x, uint64_t y) { return (x >> 48) < (y >> 48); });
+            // The segment in whole chunks of 8 entries.  Its length is first rounded up to a multiple of 4; an
+            // odd number of fours puts the first four into a chunk of their own, whose other four entries the
+            // kernel never executes (flag in bit 31 of the chunk count), so that at most 3 entries of a
+            // segment are idle instead of 7.
             const size_t start = out.pairs.size();
-            out.pairs.insert(out.pairs.end(), bucket[b].begin(), bucket[b].end());
+            const size_t len = bucket[b].size(), fours = (len + 3) / 4;
+            const bool half = fours % 2 == 1;
+            size_t taken = 0;
+            if (half) {
+                for (; taken < 4 && taken < len; ++taken) out.pairs.push_back(bucket[b][taken]);
+                while ((out.pairs.size() - start) % SCONV_FLAT_CHUNK) out.pairs.push_back(pad_entry);
+            }
+            out.pairs.insert(out.pairs.end(), bucket[b].begin() + (long)taken, bucket[b].end());
             while ((out.pairs.size() - start) % SCONV_FLAT_CHUNK) out.pairs.push_back(pad_entry);
             if (start * 8 >= ((uint64_t)1 << 32)) return SCONV_ERR_RANGE;
+            const size_t chunks = (out.pairs.size() - start) / SCONV_FLAT_CHUNK;
+            if (chunks >= ((size_t)1 << 24)) return SCONV_ERR_RANGE;
             out.seg[((size_t)ws * t.nblk + b) * 2] = (uint32_t)(start * 8);
-            out.seg[((size_t)ws * t.nblk + b) * 2 + 1] = (uint32_t)((out.pairs.size() - start) / SCONV_FLAT_CHUNK);
+            out.seg[((size_t)ws * t.nblk + b) * 2 + 1] = (uint32_t)chunks | (half ? 0x80000000u : 0u);
         }
     }
     if (real != c.val.size()) return SCONV_ERR_PLAN;
@@ -615,7 +628,7 @@ int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out)
     for (int ws = 0; ws < t.wave_slots; ++ws) {
         for (int b = 0; b < t.nblk; ++b) {
             const size_t start = p.seg[((size_t)ws * t.nblk + b) * 2] / 8;
-            const size_t n = (size_t)p.seg[((size_t)ws * t.nblk + b) * 2 + 1] * SCONV_FLAT_CHUNK;
+            const size_t n = (size_t)(p.seg[((size_t)ws * t.nblk + b) * 2 + 1] & 0x7fffffffu) * SCONV_FLAT_CHUNK;
             for (size_t j = start; j < start + n; ++j) {
                 const uint32_t vb = (uint32_t)(p.pairs[j] & 0xffffffffu);
                 const uint32_t w1 = (uint32_t)(p.pairs[j] >> 32);

@@ -263,7 +263,7 @@ def test_balance_report_counts_streams_and_sees_skew():
     h = B.sconv_create_csr(layer, w, plan)
     b = B.sconv_csr_balance(h)
     assert b["nnz"] == np.count_nonzero(w)
-    assert b["nnz"] <= b["stream_entries"] < 1.06 * b["nnz"] and b["stream_entries"] % 8 == 0
+    assert b["nnz"] <= b["stream_entries"] < 1.03 * b["nnz"] and b["stream_entries"] % 4 == 0   # segments padded to fours
     n_wg, rg, nblk = 4, 16, 12   # 384 rows in tiles of 96; 256 channels in blocks of 22
     assert math.isclose(b["wave_mean"] * rg * 8, b["stream_entries"], rel_tol=1e-12)
     assert b["wave_mean"] <= b["simd_max"] <= b["wave_max"]
