@@ -138,15 +138,25 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         reads of the entries D ahead (A's tail, B's head) are issued."""
         def entry_w1(p):
             return w1(A, p) if p < n else w1(B, p - n)
-        emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
-        emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
+        def fetch_next():
+            # B was requested one chunk ago.  The wait for it (lgkmcnt(0), which also drains the LDS reads in
+            # flight) comes as late as B's first use allows, behind address computations that give those reads
+            # time to land; the request for N follows it.  (At the end of the previous chunk the same wait
+            # costs 1.4 % more.)
+            emit("s_waitcnt lgkmcnt(0)")
+            emit(f"s_load_dwordx16 s[{N}:{N + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
+            emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
         if batch:
             for j in range(n):
+                if j == max(n - D, 0):
+                    fetch_next()
                 emit(f"v_mad_u32_u16 v{VA0 + j}, {entry_w1(j + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
         for u in range(n):
             slot = u % D
             va = VA0 + (u if batch else slot)
             if not batch:
+                if u == max(n - D, 0):
+                    fetch_next()
                 emit(f"v_mad_u32_u16 v{va}, {entry_w1(u + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
             emit(f"s_set_gpr_idx_on {w1(A, u)}, gpr_idx(DST)")
             for t in range(T):
@@ -158,7 +168,6 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
                 emit("s_set_gpr_idx_off")
         if batch:
             emit("s_set_gpr_idx_off")
-        emit("s_waitcnt lgkmcnt(0)")
         emit(f"s_cmp_lg_u32 s{SOFF}, s{SCNT}")          # SCNT: the offset at which this segment's loads end
 
     # ------------------------------------------------------------------ set-up
@@ -238,12 +247,14 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_cbranch_scc1 {loop}")
     emit(f"s_branch {segdone}")                 # the chunks read ahead sit in A and B already
     emit(f"{exit1}:")                           # ... in B and N
+    emit("s_waitcnt lgkmcnt(0)")                # N may still be on its way
     for w in range(0, W, 2):
         emit(f"s_mov_b64 s[{SA + w}:{SA + w + 1}], s[{SB + w}:{SB + w + 1}]")
     for w in range(0, W, 2):
         emit(f"s_mov_b64 s[{SB + w}:{SB + w + 1}], s[{SN + w}:{SN + w + 1}]")
     emit(f"s_branch {segdone}")
     emit(f"{exit2}:")                           # ... in N and A
+    emit("s_waitcnt lgkmcnt(0)")
     for w in range(0, W, 2):
         emit(f"s_mov_b64 s[{SB + w}:{SB + w + 1}], s[{SA + w}:{SA + w + 1}]")
     for w in range(0, W, 2):
@@ -254,6 +265,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_cbranch_scc0 {exit1}")
     emit(f"s_branch {second}")
     emit(f"{segdone}:")
+    emit("s_waitcnt lgkmcnt(0)")                # the last request lands before its registers are reused
     emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
     emit(f"s_sub_u32 s{SLEFT}, s{SLEFT}, 1")
     emit(f"s_cmp_lg_u32 s{SLEFT}, 0")
