@@ -306,7 +306,33 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         emit(f"s_addc_u32 s{BASE + 2 * i + 1}, {OP['outp_hi']}, s{STMP}")
     emit("s_waitcnt vmcnt(0)")
 
+    MASKS = [28, 30, 92, 94, 96, 98]   # SGPR pairs that are free once the block loop is over
+
     def store_all(instr):
+        if T <= len(MASKS):
+            # The chunks of a lane are neighbours in the output (flat lanes: 64 positions apart; strips: the next
+            # few columns of the same row), so they are stored one after the other: pieces of one cache line
+            # written together leave L2 as whole lines.  Which lanes hold an output is decided once per chunk.
+            for t in range(T):
+                emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")   # the compare writes vcc for active lanes only
+                emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
+                emit(f"s_mov_b64 s[{MASKS[t]}:{MASKS[t] + 1}], vcc")
+            for i in range(R):
+                rowend = label("rowend")
+                emit(f"s_cmp_lt_i32 s{KROW + i}, 0")
+                emit(f"s_cbranch_scc1 {rowend}")
+                emit(f"s_mov_b64 s[{SX0}:{SX1}], s[{BASE + 2 * i}:{BASE + 2 * i + 1}]")
+                for e in range(4):
+                    if e:
+                        emit(f"s_cmp_le_u32 {OP['nimg']}, {e}")
+                        emit(f"s_cbranch_scc1 {rowend}")
+                        emit(f"s_add_u32 s{SX0}, s{SX0}, s{SPTR + 1}")
+                        emit(f"s_addc_u32 s{SX1}, s{SX1}, 0")
+                    for t in range(T):
+                        emit(f"s_mov_b64 exec, s[{MASKS[t]}:{MASKS[t] + 1}]")
+                        emit(f"{instr} v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
+                emit(f"{rowend}:")
+            return
         for t in range(T):
             emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")   # the compare writes vcc for active lanes only
             emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
