@@ -635,8 +635,8 @@ extern "C" void sconv_machine_gfx950(sconv_machine *m)
     m->fma_flops = 73.5e12;         // v_fma_f32, 256 CUs x 60 lanes-FMA/clk x 2.4 GHz x 2
     m->lds_bytes_per_s = 148e12;    // aligned ds_read_b128, 242 B/clk/CU
     m->lds_bytes_per_fma = 4.0;
-    m->lane_efficiency = 0.65;      // 0.85 (lanes that are outputs) x 0.77 (issue slots left after address
-                                    // arithmetic, LDS waits and barriers): the x = 1 plateau of 45-53 TFLOP/s
+    m->lane_efficiency = 0.73;      // 0.9 (lanes that are outputs) x 0.8 (issue slots left after address
+                                    // arithmetic, LDS waits and barriers): the x = 1 plateau of 53-55 TFLOP/s
 }
 
 extern "C" int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,

@@ -87,6 +87,25 @@ def main() -> int:
             for c in sorted(cs):
                 lines.append(f"  {c:28s} " + "  ".join(f"{l} {cs[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
             lines.append("")
+    # rates derived from the counters, beside the ceilings measured by the microbenchmark
+    # (`paper_1608_01409_amd/sconv_ceilings`: v_fma_f32 60 lanes-FMA/clk/CU, ds_read_b128 242 B/clk/CU, copy 4.9 TB/s)
+    sq1, sq2 = counters(raw, "sq1"), counters(raw, "sq2")
+    if sq1 and sq2 and "GRBM_GUI_ACTIVE" in sq1:
+        lines.append("derived per layer (kernel cycles = GRBM_GUI_ACTIVE / 8 XCDs; SQ instruction counters are per wave, "
+                     "x64 lanes; one LDS instruction of this kernel moves 1 KiB)")
+        lines.append(f"  {'layer':6s} {'us@2.4GHz':>10s} {'FMA lanes/clk/CU':>17s} {'of 64':>6s} {'LDS B/clk/CU':>13s} {'VALU busy':>10s} "
+                     f"{'HBM TB/s':>9s} {'bank conflict cyc':>18s}")
+        for l in LAYERS:
+            cyc = sq1["GRBM_GUI_ACTIVE"]["layers"].get(l, 0.0) / 8.0
+            if cyc <= 0:
+                continue
+            fma = sq2.get("SQ_INSTS_VALU_FMA_F32", {"layers": {}})["layers"].get(l, 0.0) * 64.0 / (cyc * 256.0)
+            lds = sq2.get("SQ_INSTS_LDS", {"layers": {}})["layers"].get(l, 0.0) * 1024.0 / (cyc * 256.0)
+            busy = sq1.get("SQ_ACTIVE_INST_VALU", {"layers": {}})["layers"].get(l, 0.0) * 4.0 / (cyc * 1024.0)
+            hbm = traffic.get(l, {}).get("bytes", 0) / (cyc / 2.4e9) / 1e12 if traffic else 0.0
+            bc = sq2.get("SQ_LDS_BANK_CONFLICT", {"layers": {}})["layers"].get(l, 0.0)
+            lines.append(f"  {l:6s} {cyc/2.4e3:10.1f} {fma:17.2f} {fma/64:6.1%} {lds:13.1f} {busy:10.1%} {hbm:9.2f} {bc:18.0f}")
+        lines.append("")
     text = "\n".join(lines)
     print(text)
     open(os.path.join(out_dir, "_summary_body.txt"), "w").write(text)

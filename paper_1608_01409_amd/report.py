@@ -4,7 +4,7 @@ roofline model's prediction and the dense-convolution crossover (Section 2.2,
 Section 3.2 / Figure 5 of the paper), the skewed guided-pruning-like patterns,
 and the GoogLeNet-like and strided layers.
 
-    python -m paper_1608_01409_amd.report sweep|skewed|extra|onebyone|fc|all [--iters K]
+    python -m paper_1608_01409_amd.report latency|sweep|skewed|extra|onebyone|fc|all [--iters K]
 
 Every input is seeded and synthetic (paper_1608_01409_amd/workloads.py).  The
 dense reference is the vendor's fp32 convolution reached through
@@ -115,10 +115,43 @@ def report_sweep(iters):
         m.dense_flops = flops_dense / t_dense
         pm = B.sconv_model_predict(layer, N, 0.1, None, m)
         ratio = (xc / pm["x_lower"]) if xc else None
-        print(f"{name}: measured crossover x = {xc}, model x_lower = {pm['x_lower']:.3f} (alpha {pm['alpha']:.2f}, "
-              f"dense {m.dense_flops/1e12:.1f} TFLOP/s measured), model x_upper = {pm['x_upper']:.4f}, ratio {ratio}")
+        # alpha as the paper measures it (Section 3.2): dense rate over the sparse kernel's rate at x = 1
+        alpha_meas = (flops_dense / t_dense) / (flops_dense / ts[-1])
+        print(f"{name}: measured crossover x = {xc}, model x_lower = {pm['x_lower']:.3f} (alpha {pm['alpha']:.2f} from the "
+              f"ceilings, {alpha_meas:.2f} from the x = 1 plateau; dense {m.dense_flops/1e12:.1f} TFLOP/s measured), "
+              f"model x_upper = {pm['x_upper']:.4f}, ratio {ratio}")
         emit(dict(report="crossover", layer=name, measured=xc, model_x_lower=pm["x_lower"], model_x_upper=pm["x_upper"],
-                  alpha=pm["alpha"], dense_tflops=m.dense_flops / 1e12, ratio=ratio))
+                  alpha=pm["alpha"], alpha_from_plateau=alpha_meas, dense_tflops=m.dense_flops / 1e12, ratio=ratio))
+
+
+def report_latency():
+    """Configuration 1: one image through conv3, the latency case.  Median of 200 single launches, each
+    bracketed by its own pair of events, after 20 warm-up launches."""
+    print("# latency: conv3, batch 1, density 0.10 (configuration 1)")
+    name, N, dens = wl.CONFIGS[0][0]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(0, 0, layer, N, dens)
+    xd = torch.from_numpy(x).cuda()
+    h = B.sconv_create_csr(layer, w)
+    out = B.sconv_forward(h, xd)
+    for _ in range(20):
+        B.sconv_forward(h, xd, out)
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(200):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.sconv_forward(h, xd, out)
+        e1.record()
+        e1.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    med = float(np.median(ts))
+    info = B.sconv_csr_info(h)
+    flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
+    print(f"{name}: N {N} nnz {info['nnz']}: median {med*1e3:.1f} us (min {min(ts)*1e3:.1f}), {flops/med/1e6:.1f} GFLOP/s, "
+          f"plan {info['plan']}")
+    emit(dict(report="latency", layer=name, N=N, nnz=info["nnz"], median_us=med * 1e3, min_us=min(ts) * 1e3,
+              gflops=flops / med / 1e6, plan=info["plan"]))
 
 
 def report_skewed(iters):
@@ -198,13 +231,15 @@ def report_fc(iters):
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["sweep", "skewed", "extra", "onebyone", "fc", "all"])
+    ap.add_argument("what", choices=["latency", "sweep", "skewed", "extra", "onebyone", "fc", "all"])
     ap.add_argument("--iters", type=int, default=20)
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("report: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.what in ("latency", "all"):
+        report_latency()
     if args.what in ("sweep", "all"):
         report_sweep(args.iters)
     if args.what in ("skewed", "all"):
