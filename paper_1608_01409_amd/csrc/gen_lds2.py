@@ -151,6 +151,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
                 if j == max(n - D, 0):
                     fetch_next()
                 emit(f"v_mad_u32_u16 v{VA0 + j}, {entry_w1(j + D)}, 16, v{VLB} op_sel:[1,0,0,0]")
+        emit("s_setprio 2")                       # a wave multiplying goes before one that is between chunks or staging
         for u in range(n):
             slot = u % D
             va = VA0 + (u if batch else slot)
@@ -168,6 +169,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
                 emit("s_set_gpr_idx_off")
         if batch:
             emit("s_set_gpr_idx_off")
+        emit("s_setprio 0")
         emit(f"s_cmp_lg_u32 s{SOFF}, s{SCNT}")          # SCNT: the offset at which this segment's loads end
 
     # ------------------------------------------------------------------ set-up
