@@ -258,7 +258,7 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     if (splits > 1) {
         // every part stores its partial results and a launch of its own adds them up
         const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
-        us += 4.0 + 2.0 * splits * out_bytes / 4.0e6;
+        us += 4.0 + splits * out_bytes / 4.0e6; // (the parts' own stores overlap with other workgroups' arithmetic)
     }
     return us;
 }
