@@ -5,10 +5,11 @@ layer's kernel, which bench.py reports as roofline.traffic).
 
     python -m paper_1608_01409_amd.profile_summary RAW_DIR OUT_DIR
 
-RAW_DIR holds one sub-directory per profiler run, named as in profiles/README.md:
-kt (kernel trace + stats), fetch (FETCH_SIZE), write (WRITE_SIZE), sq1, sq2
-(SQ counters).  The byte counters are scaled by what the same counter reads for
-the plain device copy bench.py launches with --copy-probe-mb (a kernel that
+RAW_DIR holds one sub-directory per profiler run, named as in the header of the
+kernel summary under profiles/: kt (kernel trace + stats), fetch (FETCH_SIZE),
+write (WRITE_SIZE), sq1, sq2 (SQ counters), l2 (TCC request counters).  The byte
+counters and the L2 request counters are scaled by what the same counter reads
+for the plain device copy bench.py launches with --copy-probe-mb (a kernel that
 moves a known number of bytes each way).
 """
 from __future__ import annotations
@@ -87,6 +88,20 @@ def main() -> int:
             for c in sorted(cs):
                 lines.append(f"  {c:28s} " + "  ".join(f"{l} {cs[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
             lines.append("")
+    l2 = counters(raw, "l2")
+    l2_read_bytes = {}
+    if l2 and "TCC_READ_sum" in l2 and l2["TCC_READ_sum"]["copy"]:
+        per_req = COPY_MB * 2.0 ** 20 / l2["TCC_READ_sum"]["copy"]
+        lines.append(f"L2 (TCC) counters per launch; one read request = {per_req:.1f} B (from the {COPY_MB} MiB copy)")
+        for c in sorted(l2):
+            lines.append(f"  {c:28s} " + "  ".join(f"{l} {l2[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
+        for l in LAYERS:
+            l2_read_bytes[l] = l2["TCC_READ_sum"]["layers"].get(l, 0.0) * per_req
+        if "TCC_HIT_sum" in l2 and "TCC_MISS_sum" in l2:
+            hr = {l: l2["TCC_HIT_sum"]["layers"].get(l, 0.0) /
+                  max(1.0, l2["TCC_HIT_sum"]["layers"].get(l, 0.0) + l2["TCC_MISS_sum"]["layers"].get(l, 0.0)) for l in LAYERS}
+            lines.append("  hit rate                     " + "  ".join(f"{l} {hr[l]:.1%}" for l in LAYERS))
+        lines.append("")
     # rates derived from the counters, beside the ceilings measured by the microbenchmark
     # (`paper_1608_01409_amd/sconv_ceilings`: v_fma_f32 60 lanes-FMA/clk/CU, ds_read_b128 242 B/clk/CU, copy 4.9 TB/s)
     sq1, sq2 = counters(raw, "sq1"), counters(raw, "sq2")
@@ -94,7 +109,7 @@ def main() -> int:
         lines.append("derived per layer (kernel cycles = GRBM_GUI_ACTIVE / 8 XCDs; SQ instruction counters are per wave, "
                      "x64 lanes; one LDS instruction of this kernel moves 1 KiB)")
         lines.append(f"  {'layer':6s} {'us@2.4GHz':>10s} {'FMA lanes/clk/CU':>17s} {'of 64':>6s} {'LDS B/clk/CU':>13s} {'VALU busy':>10s} "
-                     f"{'HBM TB/s':>9s} {'bank conflict cyc':>18s}")
+                     f"{'HBM TB/s':>9s} {'L2 read TB/s':>13s} {'bank conflict cyc':>18s}")
         for l in LAYERS:
             cyc = sq1["GRBM_GUI_ACTIVE"]["layers"].get(l, 0.0) / 8.0
             if cyc <= 0:
@@ -104,7 +119,8 @@ def main() -> int:
             busy = sq1.get("SQ_ACTIVE_INST_VALU", {"layers": {}})["layers"].get(l, 0.0) * 4.0 / (cyc * 1024.0)
             hbm = traffic.get(l, {}).get("bytes", 0) / (cyc / 2.4e9) / 1e12 if traffic else 0.0
             bc = sq2.get("SQ_LDS_BANK_CONFLICT", {"layers": {}})["layers"].get(l, 0.0)
-            lines.append(f"  {l:6s} {cyc/2.4e3:10.1f} {fma:17.2f} {fma/64:6.1%} {lds:13.1f} {busy:10.1%} {hbm:9.2f} {bc:18.0f}")
+            l2bw = l2_read_bytes.get(l, 0.0) / (cyc / 2.4e9) / 1e12
+            lines.append(f"  {l:6s} {cyc/2.4e3:10.1f} {fma:17.2f} {fma/64:6.1%} {lds:13.1f} {busy:10.1%} {hbm:9.2f} {l2bw:13.2f} {bc:18.0f}")
         lines.append("")
     text = "\n".join(lines)
     print(text)
