@@ -30,6 +30,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", type=int, default=0,
+                    help="during set-up let sconv_tune time this many candidate tilings per layer and keep the "
+                         "fastest (0: the cost model's choice)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for "
                          "scaling the HBM byte counters of a profiler run)")
@@ -59,6 +62,8 @@ def main() -> int:
         info = B.sconv_csr_info(h)
         xd = torch.from_numpy(x).cuda()
         out = torch.empty((N, layer.K, info["OH"], info["OW"]), dtype=torch.float32, device="cuda")
+        if args.tune > 0:
+            B.sconv_tune(h, xd, out, max_plans=args.tune, stream=stream)
         flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
         dense_flops = 2.0 * layer.K * layer.Cg * layer.R * layer.S * info["OH"] * info["OW"] * N
         layers.append(dict(name=name, layer=layer, N=N, h=h, x=xd, out=out, flops=flops, dense_flops=dense_flops,

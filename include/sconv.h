@@ -171,6 +171,26 @@ int sconv_fc_forward(sconv_csr *h, const float *in_t, float *out_t, int32_t N, c
 /* The tiling sconv_fc_forward uses for batch N (packs for it if it has not yet). */
 int sconv_fc_plan(sconv_csr *h, int32_t N, sconv_plan *plan);
 
+/* ---- measured choice of the tiling -------------------------------------------- */
+
+/*
+ * The tiling of a layer (channel block, workgroup size, rows per wave, bands,
+ * strips, channel splits) is chosen by a cost model (the blocking parameters
+ * Section 2.1 leaves to tuning).  sconv_tune runs the `max_plans` tilings the
+ * model ranks best for batch size N (1..32; <= 0 means 8) on the caller's
+ * buffers, timing each with events on `hip_stream`, and keeps the fastest for
+ * later sconv_forward / sconv_forward_fused calls with this N.  `in` and `out`
+ * [device] are as for sconv_forward; on return `out` holds the layer's output.
+ * SCONV_ERR_PLAN when the handle was created with a tiling of the caller's or
+ * has no LDS path.  It packs, allocates, uploads and waits for the stream, so it
+ * belongs to set-up, not to a captured or latency-critical region.  The same
+ * rules as for sconv_forward apply to overlapping calls on one handle.
+ */
+int sconv_tune(sconv_csr *h, const float *in, float *out, int32_t N, int32_t max_plans, void *hip_stream);
+
+/* The same for sconv_fc_forward (no bias, no ReLU while timing; the choice holds for calls with either). */
+int sconv_fc_tune(sconv_csr *h, const float *in_t, float *out_t, int32_t N, int32_t max_plans, void *hip_stream);
+
 /* ---- roofline performance model (Section 2.2) ------------------------------ */
 
 /*

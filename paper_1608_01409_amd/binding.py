@@ -50,7 +50,7 @@ class sconv_balance(C.Structure):
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
            "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance",
-           "sconv_fc_forward", "sconv_fc_plan"]
+           "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune"]
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
@@ -77,6 +77,8 @@ def lib():
         L.sconv_forward_fused.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_fc_forward.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_fc_plan.argtypes = [vp, i32, C.POINTER(sconv_plan)]
+        L.sconv_tune.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.sconv_fc_tune.argtypes = [vp, vp, vp, i32, i32, vp]
         L.sconv_last_hip_error.argtypes = [vp]
         L.sconv_destroy_csr.argtypes = [vp]
         L.sconv_destroy_csr.restype = None
@@ -212,6 +214,28 @@ def sconv_forward(csr: Csr, x, out=None, stream=None):
     return out
 
 
+def sconv_tune(csr: Csr, x, out=None, max_plans=8, stream=None):
+    """Times the best-ranked tilings for this batch size on x and keeps the fastest; returns the output."""
+    import torch
+
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    L = csr.layer
+    assert tuple(x.shape[1:]) == (L.C, L.H, L.W), (tuple(x.shape), L)
+    N = x.shape[0]
+    info = sconv_csr_info(csr)
+    if out is None:
+        out = torch.empty((N, L.K, info["OH"], info["OW"]), dtype=torch.float32, device=x.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+    assert tuple(out.shape) == (N, L.K, info["OH"], info["OW"])
+    s = stream if stream is not None else torch.cuda.current_stream(x.device)
+    with torch.cuda.device(x.device):
+        rc = lib().sconv_tune(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N, int(max_plans),
+                              C.c_void_p(s.cuda_stream))
+    if rc != SCONV_OK:
+        raise SconvError(rc, f"sconv_tune (hip error {lib().sconv_last_hip_error(csr.handle)})")
+    return out
+
+
 def sconv_forward_fused(csr: Csr, x, bias=None, relu=False, out=None, stream=None):
     """sconv_forward followed, inside the kernel where it can, by out = max(out + bias[k], 0); bias: fp32 CUDA
     tensor [K] or None."""
@@ -269,6 +293,25 @@ def sconv_fc_forward(csr: Csr, x_t, bias=None, relu=False, out_t=None, stream=No
                                     C.c_void_p(s.cuda_stream))
     if rc != SCONV_OK:
         raise SconvError(rc, f"sconv_fc_forward (hip error {lib().sconv_last_hip_error(csr.handle)})")
+    return out_t
+
+
+def sconv_fc_tune(csr: Csr, x_t, out_t=None, max_plans=8, stream=None):
+    """Times the best-ranked tilings of the fully connected layer for this batch size; returns the output."""
+    import torch
+
+    L = csr.layer
+    assert x_t.is_cuda and x_t.dtype == torch.float32 and x_t.is_contiguous() and x_t.dim() == 2 and x_t.shape[0] == L.C
+    N = x_t.shape[1]
+    if out_t is None:
+        out_t = torch.empty((L.K, N), dtype=torch.float32, device=x_t.device)
+    assert out_t.is_cuda and out_t.dtype == torch.float32 and out_t.is_contiguous() and tuple(out_t.shape) == (L.K, N)
+    s = stream if stream is not None else torch.cuda.current_stream(x_t.device)
+    with torch.cuda.device(x_t.device):
+        rc = lib().sconv_fc_tune(csr.handle, C.c_void_p(x_t.data_ptr()), C.c_void_p(out_t.data_ptr()), N, int(max_plans),
+                                 C.c_void_p(s.cuda_stream))
+    if rc != SCONV_OK:
+        raise SconvError(rc, f"sconv_fc_tune (hip error {lib().sconv_last_hip_error(csr.handle)})")
     return out_t
 
 

@@ -34,10 +34,10 @@ import sys
 # consecutive cells of the plane (chunk t = the next 64 cells), w when they span a block of 64/w rows by w
 # columns (chunk t = the same rows, the next w columns).  The step is an immediate of the read instruction.
 SHAPES = [
-    (1, 16, 4, True, 64), (2, 8, 4, True, 64), (2, 12, 1, True, 64), (3, 4, 4, True, 64), (3, 6, 2, True, 64),
+    (1, 16, 4, True, 64), (2, 8, 4, True, 64), (2, 12, 1, True, 64), (3, 4, 2, True, 64), (3, 6, 2, True, 64),
     (3, 8, 1, True, 64), (4, 4, 2, True, 64), (4, 5, 1, True, 64), (5, 3, 2, True, 64), (5, 4, 1, True, 64),
     (6, 3, 1, True, 64), (7, 2, 2, False, 64), (7, 3, 1, False, 64), (13, 1, 1, False, 64),
-    (3, 4, 4, True, 9), (3, 6, 2, True, 9), (3, 8, 1, True, 9),            # 27 columns in 3 strips of 9
+    (3, 4, 2, True, 9), (3, 6, 2, True, 9), (3, 8, 1, True, 9),            # 27 columns in 3 strips of 9
     (7, 2, 2, False, 8), (7, 3, 1, False, 8),                              # 55 or 56 columns in 7 strips of 8
 ]
 CH = 8                      # entries per chunk

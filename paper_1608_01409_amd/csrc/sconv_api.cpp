@@ -1,4 +1,5 @@
 // The extern "C" surface of libsconv (see include/sconv.h) and the roofline model of Section 2.2.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -66,6 +67,8 @@ struct sconv_csr {
     DeviceLds fc_dev;
     bool fc_uploaded = false;
     std::vector<StashedPacking> fc_stash;
+    std::map<int, sconv_plan> fc_plan_of_n;  // tilings sconv_fc_tune chose, by batch size
+    size_t stash_cap = kStashed;             // packings kept besides the current one (more while tuning)
     int hip_err = 0;
 };
 
@@ -133,7 +136,7 @@ static int plan_lds(sconv_csr *h, int n)
         h->dev_lds = DeviceLds();
         h->lds_uploaded = false;
         h->has_lds = false;
-        while (h->stash.size() > kStashed) { // hipFree waits for launches that still read the arrays
+        while (h->stash.size() > h->stash_cap) { // hipFree waits for launches that still read the arrays
             release_arrays(h->stash.front().dev);
             h->stash.erase(h->stash.begin());
         }
@@ -456,14 +459,58 @@ static void release_fc(sconv_csr *h)
     h->fc_uploaded = false;
 }
 
-static int plan_fc(sconv_csr *h, int N)
+// The layer as the flat-stream kernel sees it for a batch of N: `tiles` tiles of N / tiles images, f
+// consecutive features forming one channel of f rows (a filter of f x 1 taps, one output row): the same
+// arithmetic, but a channel plane is f times larger, so that every wave of a workgroup has a part of it
+// to stage when the batch alone gives a plane of only a few hundred floats.
+static int fc_mapping(const sconv_csr *h, int N, sconv_desc &kd, int &tiles)
 {
     if (!is_fc(h->desc)) return SCONV_ERR_DESC;
     if (N < 4 || N % 4) return SCONV_ERR_BATCH;
-    if (N == h->fc_n) return SCONV_OK;
     // one wave covers at most 4 x 256 images; larger batches are cut into equal tiles
-    const int tiles = (N + 1023) / 1024;
+    tiles = (N + 1023) / 1024;
     if (N % (4 * tiles)) return SCONV_ERR_BATCH;
+    const int nc = N / tiles;
+    int f = 1;
+    if (tiles == 1)
+        for (int c : {16, 8, 4, 2})
+            if (h->desc.C % c == 0 && c * nc <= 1024) {
+                f = c;
+                break;
+            }
+    kd = h->desc;
+    kd.C = h->desc.C / f;
+    kd.H = f;
+    kd.R = f;
+    kd.W = nc / 4;
+    return SCONV_OK;
+}
+
+// What the tiling search is asked for: the fields of the plan the handle was created with are honoured
+// where they apply to this mapping.
+static sconv_plan fc_request(const sconv_csr *h)
+{
+    sconv_plan req = h->requested;
+    req.kernel = 3;
+    req.nt = 4;
+    req.band = 0;
+    req.strip = 0;
+    return req;
+}
+
+// Pack for a batch of N.  force: a complete tiling to use (sconv_fc_tune's candidates); otherwise the one
+// tuned for N if there is one, otherwise the cost model's choice.
+static int plan_fc(sconv_csr *h, int N, const sconv_plan *force = nullptr)
+{
+    sconv_desc kd;
+    int tiles;
+    int rc = fc_mapping(h, N, kd, tiles);
+    if (rc) return rc;
+    if (!force) {
+        auto tuned = h->fc_plan_of_n.find(N);
+        if (tuned != h->fc_plan_of_n.end()) force = &tuned->second;
+    }
+    if (N == h->fc_n && (!force || same_plan(*force, h->fc_flat.t.p))) return SCONV_OK;
     if (h->fc_n > 0) { // set the current packing aside; one for this batch size may be waiting there
         StashedPacking old;
         old.flat = true;
@@ -477,14 +524,14 @@ static int plan_fc(sconv_csr *h, int N)
         h->fc_dev = DeviceLds();
         h->fc_uploaded = false;
         h->fc_n = 0;
-        while (h->fc_stash.size() > kStashed) {
+        while (h->fc_stash.size() > h->stash_cap) {
             release_arrays(h->fc_stash.front().dev);
             h->fc_stash.erase(h->fc_stash.begin());
         }
     }
     for (size_t i = 0; i < h->fc_stash.size(); ++i) {
         StashedPacking &sp = h->fc_stash[i];
-        if (sp.fc_n != N) continue;
+        if (sp.fc_n != N || (force && !same_plan(*force, sp.lds_flat.t.p))) continue;
         h->fc_flat = std::move(sp.lds_flat);
         h->fc_dev = sp.dev;
         h->fc_uploaded = sp.uploaded;
@@ -494,37 +541,15 @@ static int plan_fc(sconv_csr *h, int N)
         h->fc_stash.erase(h->fc_stash.begin() + (long)i);
         return SCONV_OK;
     }
-    const int nc = N / tiles;
-    // f consecutive features form one channel of f rows (a filter of f x 1 taps, one output row): the same
-    // arithmetic, but a channel plane is f times larger, so that every wave of a workgroup has a part of
-    // it to stage when the batch alone gives a plane of only a few hundred floats
-    int f = 1;
-    if (tiles == 1)
-        for (int c : {16, 8, 4, 2})
-            if (h->desc.C % c == 0 && c * nc <= 1024) {
-                f = c;
-                break;
-            }
-    sconv_desc kd = h->desc;
-    kd.C = h->desc.C / f;
-    kd.H = f;
-    kd.R = f;
-    kd.W = nc / 4;
     Canonical kc;
     kc.rowptr = h->canon.rowptr;
     kc.colidx = h->canon.colidx;
     kc.val = h->canon.val;
     kc.off.resize(h->canon.off.size());
     for (size_t j = 0; j < kc.off.size(); ++j) kc.off[j] = h->canon.off[j] * kd.W; // feature c = row c of the wide image
-    // fields of the plan the handle was created with are honoured where they apply to this mapping
-    sconv_plan req = h->requested;
-    req.kernel = 3;
-    req.nt = 4;
-    req.band = 0;
-    req.strip = 0;
     const double avg = kd.K ? (double)kc.val.size() / kd.K : 0.0;
     LdsTiling t;
-    int rc = make_lds_tiling(kd, req, 4 * tiles, avg, t);
+    rc = make_lds_tiling(kd, force ? *force : fc_request(h), 4 * tiles, avg, t);
     if (rc) return rc;
     t.out_pos = 4; // the four images of a cell are consecutive in the output row
     rc = pack_flat(kd, kc, t, h->fc_flat);
@@ -582,6 +607,142 @@ extern "C" int sconv_fc_forward(sconv_csr *h, const float *in_t, float *out_t, i
     ep.bias = bias;
     ep.relu = relu != 0;
     return run_flat(h, h->fc_desc, t, h->fc_dev, lay, in_t, out_t, 4 * h->fc_tiles, K, N, ep, hip_stream);
+}
+
+// ---- measured choice of the tiling ----------------------------------------------------------------------
+
+// Times run() after install(candidate) for every candidate and returns the index of the fastest in *best
+// (-1 if none could be installed and run).  A candidate that cannot be packed or launched is skipped.
+// All candidates are packed and uploaded first and stay in the handle's stash, so that the timed part only
+// switches between them: the GPU's clocks drop while the host packs, and a candidate timed right after
+// that would look 10-15 % slower than one timed later.
+template <class Install, class Run>
+static int time_candidates(sconv_csr *h, const std::vector<LdsTiling> &cands, Install install, Run run, void *stream, int *best)
+{
+    *best = -1;
+    std::vector<size_t> ok;
+    for (size_t i = 0; i < cands.size(); ++i)
+        if (install(cands[i].p) == SCONV_OK && run() == SCONV_OK) ok.push_back(i);
+    if (ok.empty()) return SCONV_OK;
+    StreamTimer timer;
+    int rc = timer_create(timer, &h->hip_err);
+    if (rc) return rc;
+    // `n` runs between two events, in milliseconds per run
+    auto timed = [&](int n, float *ms) {
+        int r = timer_start(timer, stream, &h->hip_err);
+        for (int k = 0; k < n && !r; ++k) r = run();
+        if (!r) r = timer_stop_ms(timer, stream, ms, &h->hip_err);
+        *ms /= (float)n;
+        return r;
+    };
+    // warm-up, about 30 ms of the first candidate
+    float ms = 0, spent = 0;
+    rc = install(cands[ok[0]].p);
+    for (int k = 0; k < 200 && !rc && spent < 30.0f; ++k) {
+        rc = timed(4, &ms);
+        spent += 4 * ms;
+    }
+    // three rounds over the candidates, about 2 ms each; a candidate's time is its fastest round
+    std::vector<float> t(ok.size(), std::numeric_limits<float>::max());
+    for (int round = 0; round < 3 && !rc; ++round)
+        for (size_t j = 0; j < ok.size() && !rc; ++j) {
+            rc = install(cands[ok[j]].p);
+            if (!rc) rc = timed(1, &ms);
+            if (rc) break;
+            const int reps = std::max(3, std::min(40, (int)(2.0f / std::max(ms, 0.01f))));
+            rc = timed(reps, &ms);
+            if (!rc) t[j] = std::min(t[j], ms);
+        }
+    timer_destroy(timer);
+    if (rc) return rc;
+    size_t arg = 0;
+    for (size_t j = 1; j < ok.size(); ++j)
+        if (t[j] < t[arg]) arg = j;
+    *best = (int)ok[arg];
+    return SCONV_OK;
+}
+
+// The stash holds every candidate while they are timed; afterwards the oldest go.
+struct StashRoom {
+    sconv_csr *h;
+    StashRoom(sconv_csr *handle, size_t n) : h(handle) { h->stash_cap = std::max(kStashed, n); }
+    ~StashRoom()
+    {
+        h->stash_cap = kStashed;
+        while (h->stash.size() > kStashed) {
+            release_arrays(h->stash.front().dev);
+            h->stash.erase(h->stash.begin());
+        }
+        while (h->fc_stash.size() > kStashed) {
+            release_arrays(h->fc_stash.front().dev);
+            h->fc_stash.erase(h->fc_stash.begin());
+        }
+    }
+};
+
+static int clamp_plans(int max_plans) { return max_plans < 1 ? 8 : std::min(max_plans, 32); }
+
+extern "C" int sconv_tune(sconv_csr *h, const float *in, float *out, int32_t N, int32_t max_plans, void *hip_stream)
+{
+    if (!h || !in || !out) return SCONV_ERR_NULL;
+    if (N < 1) return SCONV_ERR_BATCH;
+    const sconv_plan &rq = h->requested;
+    const bool free_choice = !rq.nt && !rq.cb && !rq.waves && !rq.cg && !rq.rows_w && !rq.t && !rq.band && !rq.strip && !rq.splits;
+    if (!h->has_lds || !free_choice) return SCONV_ERR_PLAN;
+    const int n_plan = N < 4 ? 4 : N;
+    const Epilogue none;
+    try {
+        const double avg = h->kdesc.K ? (double)h->canon.val.size() / h->kdesc.K : 0.0;
+        std::vector<LdsTiling> cands;
+        int rc = rank_lds_tilings(h->kdesc, h->requested, n_plan, avg, clamp_plans(max_plans), cands);
+        if (rc) return rc;
+        int best = -1;
+        StashRoom room(h, cands.size());
+        rc = time_candidates(
+            h, cands,
+            [&](const sconv_plan &p) {
+                h->plan_of_n[n_plan] = p;
+                return plan_lds(h, n_plan);
+            },
+            [&]() { return forward_impl(h, in, out, N, none, hip_stream); }, hip_stream, &best);
+        // the fastest, or the cost model's choice if nothing could be timed
+        h->plan_of_n[n_plan] = cands[best < 0 ? 0 : (size_t)best].p;
+        const int prc = plan_lds(h, n_plan);
+        if (rc) return rc;
+        if (prc) return prc;
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    return forward_impl(h, in, out, N, none, hip_stream);
+}
+
+extern "C" int sconv_fc_tune(sconv_csr *h, const float *in_t, float *out_t, int32_t N, int32_t max_plans, void *hip_stream)
+{
+    if (!h || !in_t || !out_t) return SCONV_ERR_NULL;
+    if (N < 1) return SCONV_ERR_BATCH;
+    try {
+        sconv_desc kd;
+        int tiles;
+        int rc = fc_mapping(h, N, kd, tiles);
+        if (rc) return rc;
+        const double avg = kd.K ? (double)h->canon.val.size() / kd.K : 0.0;
+        std::vector<LdsTiling> cands;
+        rc = rank_lds_tilings(kd, fc_request(h), 4 * tiles, avg, clamp_plans(max_plans), cands);
+        if (rc) return rc;
+        int best = -1;
+        StashRoom room(h, cands.size());
+        h->fc_plan_of_n.erase(N);
+        rc = time_candidates(
+            h, cands, [&](const sconv_plan &p) { return plan_fc(h, N, &p); },
+            [&]() { return sconv_fc_forward(h, in_t, out_t, N, nullptr, 0, hip_stream); }, hip_stream, &best);
+        if (rc) return rc;
+        h->fc_plan_of_n[N] = cands[best < 0 ? 0 : (size_t)best].p;
+        rc = plan_fc(h, N); // while the candidates' packings are still at hand
+        if (rc) return rc;
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    return sconv_fc_forward(h, in_t, out_t, N, nullptr, 0, hip_stream);
 }
 
 extern "C" int sconv_last_hip_error(const sconv_csr *h) { return h ? h->hip_err : 0; }

@@ -250,25 +250,68 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
     const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
     double eff = wps >= 4 ? 0.78 : wps >= 3 ? 0.72 : wps >= 2 ? 0.68 : 0.42;
-    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.86; // shallow read-ahead ring
+    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.93; // shallow read-ahead ring
     const double simd_clk = t.p.waves * entries * (4.0 * t.p.t + 1.7); // VALU clocks per SIMD, one workgroup
-    double group = m * simd_clk / eff + blocks * 1500.0 + 14000.0;
+    // per channel block: the barrier and the refill of the read pipeline, which a second workgroup on the CU
+    // fills, and what the staging of the block (L2 to LDS, every workgroup its own copy) takes from the loop;
+    // per workgroup: prologue and stores, partly filled by a second workgroup as well
+    const double block_bytes = (double)t.p.cb * t.plane_cells * 16.0;
+    double group = m * simd_clk / eff + blocks * (800.0 / m + m * block_bytes / 120.0) + (m >= 2 ? (t.p.waves >= 8 ? 8000.0 : 10500.0) : 14000.0);
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
     double us = std::ceil(cu_wgs / m) * group / 2400.0;
     if (splits > 1) {
         // every part stores its partial results and a launch of its own adds them up
         const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
-        us += 4.0 + splits * out_bytes / 4.0e6; // (the parts' own stores overlap with other workgroups' arithmetic)
+        us += 4.0 + splits * (out_bytes / 4.0e6 + 0.3); // the reduction reads every part: bandwidth, and latency per part
     }
     return us;
 }
 
+static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
+                              std::vector<std::pair<double, LdsTiling>> *all);
+
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
+{
+    return search_lds_tilings(d, req, N_hint, avg_row_nnz, out, nullptr);
+}
+
+static bool same_tiling(const sconv_plan &a, const sconv_plan &b)
+{
+    return a.kernel == b.kernel && a.nt == b.nt && a.cb == b.cb && a.waves == b.waves && a.cg == b.cg &&
+           a.rows_w == b.rows_w && a.t == b.t && a.band == b.band && a.strip == b.strip && a.splits == b.splits;
+}
+
+int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
+                     std::vector<LdsTiling> &out)
+{
+    std::vector<std::pair<double, LdsTiling>> all;
+    LdsTiling best;
+    const int rc = search_lds_tilings(d, req, N_hint, avg_row_nnz, best, &all);
+    if (rc) return rc;
+    std::stable_sort(all.begin(), all.end(), [](const std::pair<double, LdsTiling> &a, const std::pair<double, LdsTiling> &b) {
+        return a.first < b.first;
+    });
+    out.clear();
+    for (const auto &c : all) {
+        if ((int)out.size() >= max_out) break;
+        bool seen = false;
+        for (const auto &o : out) seen = seen || same_tiling(o.p, c.second.p);
+        if (!seen) out.push_back(c.second);
+    }
+    return out.empty() ? SCONV_ERR_PLAN : SCONV_OK;
+}
+
+static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
+                              std::vector<std::pair<double, LdsTiling>> *all)
 {
     const Geometry g = geometry(d);
     if (d.stride != 1) return SCONV_ERR_PLAN;
     const bool full = req.nt && req.cb && req.waves && req.cg && req.rows_w && req.t;
-    if (full) return fill_tiling(d, req, out);
+    if (full) {
+        const int rc = fill_tiling(d, req, out);
+        if (!rc && all) all->emplace_back(0.0, out);
+        return rc;
+    }
     if (req.strip && req.kernel && req.kernel != 3) return SCONV_ERR_PLAN;
     const int kinds[2] = {3, 1};
 
@@ -318,6 +361,7 @@ int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, doub
                         if (!req.splits && t.p.splits != sp) continue; // the same as a smaller choice
                         const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
                                                    : tiling_cost(d, t, N_hint, avg_row_nnz);
+                        if (all) all->emplace_back(c, t);
                         if (best < 0 || c < best) {
                             best = c;
                             out = t;

@@ -104,6 +104,9 @@ int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, cons
 // Fill in a tiling for the LDS kernel (fields of `req` that are 0 are chosen).  N_hint is the
 // batch size the choice is tuned for.  Returns SCONV_ERR_PLAN if the layer cannot use it.
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out);
+// The max_out distinct tilings the cost model ranks best, best first (out[0] is make_lds_tiling's choice).
+int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
+                     std::vector<LdsTiling> &out);
 // p.kernel selects the shape list: 1 = per-row streams, 3 = flat streams (nt must be 4)
 bool lds_kernel_available(int vec, int t, int rows_w);
 
@@ -166,5 +169,14 @@ int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in,
                   void *stream, int *hip_err);
 int upload(const void *host, size_t bytes, void **dev, int *hip_err);
 void release(void *dev);
+
+// A pair of events that brackets work on one stream (for sconv_tune); stop waits for the stream.
+struct StreamTimer {
+    void *e0 = nullptr, *e1 = nullptr;
+};
+int timer_create(StreamTimer &t, int *hip_err);
+int timer_start(StreamTimer &t, void *stream, int *hip_err);
+int timer_stop_ms(StreamTimer &t, void *stream, float *ms, int *hip_err);
+void timer_destroy(StreamTimer &t);
 
 } // namespace sconv

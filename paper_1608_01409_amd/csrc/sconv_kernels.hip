@@ -422,6 +422,53 @@ void release(void *dev)
     if (dev) (void)hipFree(dev);
 }
 
+int timer_create(StreamTimer &t, int *hip_err)
+{
+    t.e0 = t.e1 = nullptr;
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) {
+        e = hipEventCreate(&e1);
+        if (e != hipSuccess) (void)hipEventDestroy(e0);
+    }
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    t.e0 = e0;
+    t.e1 = e1;
+    return SCONV_OK;
+}
+
+int timer_start(StreamTimer &t, void *stream, int *hip_err)
+{
+    const hipError_t e = hipEventRecord(static_cast<hipEvent_t>(t.e0), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+int timer_stop_ms(StreamTimer &t, void *stream, float *ms, int *hip_err)
+{
+    hipError_t e = hipEventRecord(static_cast<hipEvent_t>(t.e1), static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = hipEventSynchronize(static_cast<hipEvent_t>(t.e1));
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, static_cast<hipEvent_t>(t.e0), static_cast<hipEvent_t>(t.e1));
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
+void timer_destroy(StreamTimer &t)
+{
+    if (t.e0) (void)hipEventDestroy(static_cast<hipEvent_t>(t.e0));
+    if (t.e1) (void)hipEventDestroy(static_cast<hipEvent_t>(t.e1));
+    t.e0 = t.e1 = nullptr;
+}
+
 template <int VEC, int T, int ROWS_W>
 static int launch_lds_inst(const LdsArgs &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
 {

@@ -4,7 +4,7 @@ roofline model's prediction and the dense-convolution crossover (Section 2.2,
 Section 3.2 / Figure 5 of the paper), the skewed guided-pruning-like patterns,
 and the GoogLeNet-like and strided layers.
 
-    python -m paper_1608_01409_amd.report latency|sweep|skewed|extra|onebyone|fc|all [--iters K]
+    python -m paper_1608_01409_amd.report latency|sweep|skewed|extra|onebyone|fc|tune|all [--iters K]
 
 Every input is seeded and synthetic (paper_1608_01409_amd/workloads.py).  The
 dense reference is the vendor's fp32 convolution reached through
@@ -32,6 +32,8 @@ def time_gpu(fn, iters: int, warm: int = 3, warm_ms: float = 30.0) -> float:
     to a low clock state and the first milliseconds of work run well below the sustained rate."""
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
+    fn()                       # a first call may pack and upload: keep that out of the estimate below
+    torch.cuda.synchronize()
     e0.record()
     for _ in range(warm):
         fn()
@@ -229,9 +231,49 @@ def report_fc(iters):
         emit(row)
 
 
+TUNE_CASES = [("conv2", 256, 0.1), ("conv3", 256, 0.1), ("conv4", 256, 0.1), ("conv5", 256, 0.1), ("conv3", 64, 0.1),
+              ("conv3", 16, 0.1), ("conv3", 1, 0.1), ("conv5", 64, 0.1), ("conv2", 64, 0.1), ("goog3x3", 64, 0.2),
+              ("goog5x5", 64, 0.3), ("conv1", 64, 0.3)]
+
+
+def report_tune(iters, max_plans=24):
+    """The cost model's tiling against the measured choice (sconv_tune / sconv_fc_tune) on one box."""
+    print(f"# tiling chosen by the cost model against the fastest of its {max_plans} best-ranked tilings, timed (sconv_tune)")
+    for i, (name, N, dens) in enumerate(TUNE_CASES):
+        layer = wl.LAYERS[name]
+        x, w = wl.make_case(1, i, layer, N, dens)
+        xd = torch.from_numpy(x).cuda()
+        h = B.sconv_create_csr(layer, w)
+        out = B.sconv_forward(h, xd)
+        ms0 = time_gpu(lambda: B.sconv_forward(h, xd, out), iters)
+        p0 = B.sconv_csr_info(h)["plan"]
+        B.sconv_tune(h, xd, out, max_plans)
+        ms1 = time_gpu(lambda: B.sconv_forward(h, xd, out), iters)
+        p1 = B.sconv_csr_info(h)["plan"]
+        print(f"{name} N {N}: model's choice {ms0*1e3:.1f} us, tuned {ms1*1e3:.1f} us ({100*(ms1/ms0-1):+.1f} %)"
+              f"{'' if p0 == p1 else f', {p0} -> {p1}'}")
+        emit(dict(report="tune", layer=name, N=N, density=dens, t_model_choice_us=ms0 * 1e3, t_tuned_us=ms1 * 1e3,
+                  plan_model=p0, plan_tuned=p1))
+    for i, (name, N, dens) in enumerate(wl.FC_CONFIG):
+        C_in, K = wl.FC_LAYERS[name]
+        x_t, w = wl.make_fc_case(i, name, N, dens)
+        xd = torch.from_numpy(x_t).cuda()
+        h = B.sconv_create_csr(B.fc_layer(C_in, K), w.reshape(K, C_in, 1, 1), dict(kernel=2))
+        out = B.sconv_fc_forward(h, xd)
+        ms0 = time_gpu(lambda: B.sconv_fc_forward(h, xd, None, False, out), iters)
+        p0 = B.sconv_fc_plan(h, N)
+        B.sconv_fc_tune(h, xd, out, max_plans)
+        ms1 = time_gpu(lambda: B.sconv_fc_forward(h, xd, None, False, out), iters)
+        p1 = B.sconv_fc_plan(h, N)
+        print(f"{name} N {N}: model's choice {ms0*1e3:.1f} us, tuned {ms1*1e3:.1f} us ({100*(ms1/ms0-1):+.1f} %)"
+              f"{'' if p0 == p1 else f', {p0} -> {p1}'}")
+        emit(dict(report="tune", layer=name, N=N, density=dens, t_model_choice_us=ms0 * 1e3, t_tuned_us=ms1 * 1e3,
+                  plan_model=p0, plan_tuned=p1))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["latency", "sweep", "skewed", "extra", "onebyone", "fc", "all"])
+    ap.add_argument("what", choices=["latency", "sweep", "skewed", "extra", "onebyone", "fc", "tune", "all"])
     ap.add_argument("--iters", type=int, default=20)
     args = ap.parse_args()
     if not torch.cuda.is_available():
@@ -251,6 +293,8 @@ def main() -> int:
                                     "when x_upper >= x_lower")
     if args.what in ("fc", "all"):
         report_fc(args.iters)
+    if args.what in ("tune", "all"):
+        report_tune(args.iters)
     return 0
 
 
