@@ -262,7 +262,7 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     if (splits > 1) {
         // every part stores its partial results and a launch of its own adds them up
         const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
-        us += 4.0 + splits * (out_bytes / 4.0e6 + 0.3); // the reduction reads every part: bandwidth, and latency per part
+        us += 4.0 + splits * (out_bytes / 3.5e6 + 0.3); // the reduction reads every part: bandwidth, and latency per part
     }
     return us;
 }
