@@ -178,8 +178,9 @@ int sconv_fc_plan(sconv_csr *h, int32_t N, sconv_plan *plan);
  * strips, channel splits) is chosen by a cost model (the blocking parameters
  * Section 2.1 leaves to tuning).  sconv_tune runs the `max_plans` tilings the
  * model ranks best for batch size N (1..32; <= 0 means 8) on the caller's
- * buffers, timing each with events on `hip_stream`, and keeps the fastest for
- * later sconv_forward / sconv_forward_fused calls with this N.  `in` and `out`
+ * buffers, timing each with events on `hip_stream`, and keeps the fastest (the
+ * model's own choice unless another is at least 1.5 % faster) for later
+ * sconv_forward / sconv_forward_fused calls with this N.  `in` and `out`
  * [device] are as for sconv_forward; on return `out` holds the layer's output.
  * SCONV_ERR_PLAN when the handle was created with a tiling of the caller's or
  * has no LDS path.  It packs, allocates, uploads and waits for the stream, so it
