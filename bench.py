@@ -146,6 +146,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "AlexNet conv2-conv5, batch 256, fp32, Bernoulli masks at density 0.10", "global_batch": 256,
+                   "tiling": f"fastest of {args.tune} candidates timed during set-up" if args.tune > 0 else "cost model",
                    "dense_equivalent_gflops": round(sum(L["dense_flops"] for L in layers) / (ms_per_step * 1e-3) / 1e9, 1)},
         "roofline": roofline, "cpu_baseline": cpu}))
     return 0
