@@ -67,6 +67,17 @@ def time_dense(layer, xd, iters):
     return time_gpu(fn, iters, warm=5)
 
 
+def time_dense_gemm(layer, N, iters):
+    """The paper's proxy for dense convolution (Section 3.2): the vendor's fp32 matrix product of the lowered
+    shapes, per group [Kg x Cg*R*S] x [Cg*R*S x OH*OW*N]; the lowering itself is not timed."""
+    torch.backends.cuda.matmul.allow_tf32 = False
+    kdim, cols = layer.Cg * layer.R * layer.S, layer.OH * layer.OW * N
+    a = torch.randn((layer.Kg, kdim), device="cuda") * 0.01
+    b = torch.randn((kdim, cols), device="cuda")
+    c = torch.empty((layer.Kg, cols), device="cuda")
+    return layer.groups * time_gpu(lambda: torch.matmul(a, b, out=c), iters, warm=5)
+
+
 def crossover(xs, t_sparse, t_dense):
     """Density at which the sparse time reaches the dense time: log-linear interpolation between the two
     sweep points that bracket it; None if sparse stays faster (or slower) over the whole sweep."""
@@ -93,7 +104,9 @@ def report_sweep(iters):
         xs, ts = [], []
         x0, _ = wl.make_case(2, li, layer, N, 0.1)
         xd = torch.from_numpy(x0).cuda()
-        t_dense = time_dense(layer, xd, iters) * 1e-3
+        t_conv, t_gemm = time_dense(layer, xd, iters) * 1e-3, time_dense_gemm(layer, N, iters) * 1e-3
+        t_dense = min(t_conv, t_gemm)   # the faster of the vendor's convolution and its matrix product of the lowered shapes
+        print(f"{name}: dense fp32 convolution {t_conv*1e6:.1f} us, matrix product of the lowered shapes {t_gemm*1e6:.1f} us")
         pred1 = None
         for dens in wl.SWEEP_DENSITIES:
             _, w = wl.make_case(2, li, layer, 1, dens)
@@ -123,7 +136,8 @@ def report_sweep(iters):
               f"ceilings, {alpha_meas:.2f} from the x = 1 plateau; dense {m.dense_flops/1e12:.1f} TFLOP/s measured), "
               f"model x_upper = {pm['x_upper']:.4f}, ratio {ratio}")
         emit(dict(report="crossover", layer=name, measured=xc, model_x_lower=pm["x_lower"], model_x_upper=pm["x_upper"],
-                  alpha=pm["alpha"], alpha_from_plateau=alpha_meas, dense_tflops=m.dense_flops / 1e12, ratio=ratio))
+                  alpha=pm["alpha"], alpha_from_plateau=alpha_meas, dense_tflops=m.dense_flops / 1e12, ratio=ratio,
+                  t_dense_conv_us=t_conv * 1e6, t_dense_gemm_us=t_gemm * 1e6))
 
 
 def report_latency():
