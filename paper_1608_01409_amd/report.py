@@ -200,16 +200,18 @@ def report_extra(iters, cfg=4, title="# GoogLeNet-inception-like and strided lay
         x, w = wl.make_case(cfg, li, layer, N, dens)
         xd = torch.from_numpy(x).cuda()
         ms, info, h = time_sparse(layer, w, xd, iters)
-        t_dense = time_dense(layer, xd, iters)
+        t_conv, t_gemm = time_dense(layer, xd, iters), time_dense_gemm(layer, N, iters)
+        t_dense = min(t_conv, t_gemm)
         flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
         pred = B.sconv_model_predict(layer, N, dens, h)
         hbm = pred["bytes_act"] / (ms * 1e-3) / 1e12
         row = dict(report="extra", layer=name, N=N, density=dens, nnz=info["nnz"], t_us=ms * 1e3, tflops=flops / ms / 1e9,
-                   t_dense_us=t_dense * 1e3, speedup=t_dense / ms, t_model_us=pred["t_sparse"] * 1e6,
+                   t_dense_us=t_dense * 1e3, t_dense_conv_us=t_conv * 1e3, t_dense_gemm_us=t_gemm * 1e3,
+                   speedup=t_dense / ms, t_model_us=pred["t_sparse"] * 1e6,
                    model_bandwidth_bound=bool(pred["bandwidth_bound"]), model_x_upper=pred["x_upper"],
                    model_x_lower=pred["x_lower"], activation_tb_per_s=hbm, plan=info["plan"])
         print(f"{name}: N {N} x {dens} nnz {info['nnz']}: {ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s "
-              f"({hbm:.2f} TB/s of activations), dense {t_dense*1e3:.1f} us, speedup {t_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us "
+              f"({hbm:.2f} TB/s of activations), dense {t_dense*1e3:.1f} us (convolution {t_conv*1e3:.1f}, matrix product {t_gemm*1e3:.1f}), speedup {t_dense/ms:.2f}, model {pred['t_sparse']*1e6:.1f} us "
               f"({'bandwidth' if pred['bandwidth_bound'] else 'compute'} bound, useful x in ({pred['x_upper']:.3f}, {pred['x_lower']:.3f})), "
               f"plan {info['plan']}")
         emit(row)
