@@ -189,6 +189,15 @@ int sconv_fc_plan(sconv_csr *h, int32_t N, sconv_plan *plan);
  */
 int sconv_tune(sconv_csr *h, const float *in, float *out, int32_t N, int32_t max_plans, void *hip_stream);
 
+/*
+ * The candidates sconv_tune would time for batch size N, best-ranked first:
+ * plans[0] is the cost model's choice, the one sconv_forward uses untuned.
+ * `plans` [host] has room for max_plans entries (1..32; <= 0 means 8); *count
+ * receives how many were written.  Every one of them is a complete tiling that
+ * sconv_create_csr accepts for this layer.  No GPU is needed.
+ */
+int sconv_rank_plans(const sconv_csr *h, int32_t N, int32_t max_plans, sconv_plan *plans, int32_t *count);
+
 /* The same for sconv_fc_forward (no bias, no ReLU while timing; the choice holds for calls with either). */
 int sconv_fc_tune(sconv_csr *h, const float *in_t, float *out_t, int32_t N, int32_t max_plans, void *hip_stream);
 

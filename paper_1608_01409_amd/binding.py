@@ -50,7 +50,7 @@ class sconv_balance(C.Structure):
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
            "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance",
-           "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune"]
+           "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune", "sconv_rank_plans"]
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
@@ -78,6 +78,7 @@ def lib():
         L.sconv_fc_forward.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_fc_plan.argtypes = [vp, i32, C.POINTER(sconv_plan)]
         L.sconv_tune.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.sconv_rank_plans.argtypes = [vp, i32, i32, C.POINTER(sconv_plan), C.POINTER(i32)]
         L.sconv_fc_tune.argtypes = [vp, vp, vp, i32, i32, vp]
         L.sconv_last_hip_error.argtypes = [vp]
         L.sconv_destroy_csr.argtypes = [vp]
@@ -212,6 +213,15 @@ def sconv_forward(csr: Csr, x, out=None, stream=None):
     if rc != SCONV_OK:
         raise SconvError(rc, f"sconv_forward (hip error {lib().sconv_last_hip_error(csr.handle)})")
     return out
+
+
+def sconv_rank_plans(csr: Csr, N: int, max_plans: int = 8) -> list:
+    """The tilings sconv_tune would time for batch size N, the cost model's choice first."""
+    room = 8 if max_plans < 1 else min(int(max_plans), 32)
+    plans = (sconv_plan * room)()
+    count = C.c_int32(0)
+    _check(lib().sconv_rank_plans(csr.handle, N, int(max_plans), plans, C.byref(count)), "sconv_rank_plans")
+    return [plans[i].as_dict() for i in range(count.value)]
 
 
 def sconv_tune(csr: Csr, x, out=None, max_plans=8, stream=None):

@@ -684,6 +684,24 @@ struct StashRoom {
 
 static int clamp_plans(int max_plans) { return max_plans < 1 ? 8 : std::min(max_plans, 32); }
 
+extern "C" int sconv_rank_plans(const sconv_csr *h, int32_t N, int32_t max_plans, sconv_plan *plans, int32_t *count)
+{
+    if (!h || !plans || !count) return SCONV_ERR_NULL;
+    *count = 0;
+    if (N < 1) return SCONV_ERR_BATCH;
+    if (!h->has_lds) return SCONV_ERR_PLAN;
+    try {
+        const double avg = h->kdesc.K ? (double)h->canon.val.size() / h->kdesc.K : 0.0;
+        std::vector<LdsTiling> cands;
+        const int rc = rank_lds_tilings(h->kdesc, h->requested, N < 4 ? 4 : N, avg, clamp_plans(max_plans), cands);
+        if (rc) return rc;
+        for (const LdsTiling &t : cands) plans[(*count)++] = t.p;
+    } catch (const std::bad_alloc &) {
+        return SCONV_ERR_NOMEM;
+    }
+    return SCONV_OK;
+}
+
 extern "C" int sconv_tune(sconv_csr *h, const float *in, float *out, int32_t N, int32_t max_plans, void *hip_stream)
 {
     if (!h || !in || !out) return SCONV_ERR_NULL;

@@ -377,3 +377,34 @@ def test_random_layers_pack_and_unpack_bit_exactly(oracle, seed):
         B.sconv_fc_plan(hf, n)
         r3, o3, v3 = B.sconv_csr_unpack(hf, 3)
         assert np.array_equal(r3, er) and np.array_equal(o3, eo) and np.array_equal(v3.view(np.uint32), ev.view(np.uint32)), n
+
+
+def test_ranked_plans_start_with_the_cost_models_choice_and_all_pack():
+    """sconv_rank_plans: distinct complete tilings, the first one the tiling an untuned handle uses for that
+    batch size, every one accepted by sconv_create_csr and unpacking to the oracle's arrays."""
+    from oracle import sconv_oracle as O
+    layer = wl.small_layer("rank", C=24, H=13, W=13, K=40, R=3, S=3, stride=1, pad=1, groups=2)
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((layer.K, layer.Cg, 3, 3)) * 0.01).astype(np.float32)
+    w = np.where(rng.random(w.shape) < 0.2, w, 0).astype(np.float32)
+    rp, ci, v = O.csr_from_dense(layer, w)
+    off = O.lower_offsets(layer, rp, ci)
+    h = B.sconv_create_csr(layer, w)
+    for N in (1, 8, 256):
+        plans = B.sconv_rank_plans(h, N, 12)
+        assert 1 <= len(plans) <= 12
+        assert len({tuple(sorted(p.items())) for p in plans}) == len(plans)
+        for p in plans:
+            assert p["kernel"] == 3 and p["nt"] == 4 and all(p[k] > 0 for k in ("cb", "waves", "cg", "rows_w", "t", "band", "splits"))
+            hp = B.sconv_create_csr(layer, w, p)
+            assert B.sconv_csr_info(hp)["plan"] == p
+            urp, uoff, uv = B.sconv_csr_unpack(hp, 1)
+            assert np.array_equal(urp, rp) and np.array_equal(uoff, off) and np.array_equal(uv.view(np.uint32), v.view(np.uint32))
+    # the first candidate for the batch size a new handle is planned for is the handle's own tiling
+    assert B.sconv_rank_plans(h, 256, 4)[0] == B.sconv_csr_info(h)["plan"]
+    assert len(B.sconv_rank_plans(h, 256, 0)) <= 8 and len(B.sconv_rank_plans(h, 256, 1000)) <= 32
+    # handles without an LDS path have nothing to rank
+    hd = B.sconv_create_csr(layer, w, dict(kernel=2))
+    with pytest.raises(B.SconvError) as e:
+        B.sconv_rank_plans(hd, 8)
+    assert e.value.status == B.ERR["PLAN"]
