@@ -19,6 +19,15 @@ two FLOPs over the whole batch; S_A counts each unpadded activation once;
 S_W counts each dense weight once per call.  With Table 1's F and B these
 reproduce the section's own worked numbers (the pins in the tests).
 
+Two additions, both off by default so that the four formulas above stay as printed:
+
+* lowered=True models the comparison the section's figure draws ("conv5 lowered"): sparse convolution on
+  tensors lowered to matrices.  Lowering replicates the input (Section 2.1), so the activation bytes
+  become those of the lowered matrix, C*R*S rows by OH*OW columns per image, plus the output.  Creating
+  that matrix is not charged (the paper leaves the cost of lowering out of its dense proxy as well).
+* t_fixed is a per-call time (launch, prologue, epilogue) added to the sparse time.  It is not in the paper;
+  it is 0 unless a measured value is passed in.
+
 When alpha is not given it is derived for a machine whose sparse kernel is
 limited by either its vector multiply-add rate or the bandwidth of the on-chip
 memory its operands are read from:
@@ -31,12 +40,13 @@ from __future__ import annotations
 import math
 
 
-def layer_counts(layer, N: int):
+def layer_counts(layer, N: int, lowered: bool = False):
     Cg = layer.C // layer.groups
     OH = (layer.H + 2 * layer.pad - layer.R) // layer.stride + 1
     OW = (layer.W + 2 * layer.pad - layer.S) // layer.stride + 1
     flops = 2.0 * layer.K * Cg * layer.R * layer.S * OH * OW * N
-    s_a = 4.0 * N * (layer.C * layer.H * layer.W + layer.K * OH * OW)
+    in_elems = layer.C * layer.R * layer.S * OH * OW if lowered else layer.C * layer.H * layer.W
+    s_a = 4.0 * N * (in_elems + layer.K * OH * OW)
     s_w = 4.0 * layer.K * Cg * layer.R * layer.S
     return flops, s_a, s_w
 
@@ -46,12 +56,13 @@ def derive_alpha(F, fma_flops, lds_bytes_per_s, lds_bytes_per_fma, lane_efficien
     return F / f_sparse
 
 
-def predict(layer, N: int, x: float, F: float, B: float, alpha: float, beta: float = 2.0):
-    flops, s_a, s_w = layer_counts(layer, N)
+def predict(layer, N: int, x: float, F: float, B: float, alpha: float, beta: float = 2.0,
+            lowered: bool = False, t_fixed: float = 0.0):
+    flops, s_a, s_w = layer_counts(layer, N, lowered)
     t_dense = flops / F
     t_sc = alpha * x * flops / F
     t_sbw = (s_a + beta * x * s_w) / B
-    t_sparse = max(t_sc, t_sbw)
+    t_sparse = t_fixed + max(t_sc, t_sbw)
     # density at which compute time equals bandwidth time
     denom = alpha * flops / F - beta * s_w / B
     x_upper = (s_a / B) / denom if denom > 0 else math.inf

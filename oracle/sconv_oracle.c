@@ -99,6 +99,33 @@ int oracle_lower_offsets(const oracle_desc *d, const int32_t *rowptr,
     return 0;
 }
 
+/*
+ * The same for an HWC image (channel innermost), the other layout Section 2.1
+ * allows: any f with f(c, y+r, x+s) = f(c, y, x) + f(0, r, s) will do.  On the
+ * zero-padded HWC image f(c,y,x) = (y*Wp + x)*C + c, so the offset of weight
+ * (c, r, s) is (r*Wp + s)*C + g(k)*Cg + c, and moving the output by one row or
+ * column moves every read by stride*Wp*C or stride*C elements.
+ */
+int oracle_lower_offsets_hwc(const oracle_desc *d, const int32_t *rowptr,
+                             const int32_t *colidx, int32_t *off)
+{
+    if (!desc_ok(d) || !rowptr || !off) return -1;
+    const int Cg = d->C / d->groups, Kg = d->K / d->groups;
+    const int Wp = d->W + 2 * d->pad;
+    for (int k = 0; k < d->K; ++k) {
+        const int g = k / Kg;
+        for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
+            const int col = colidx[j];
+            const int s = col % d->S;
+            const int r = (col / d->S) % d->R;
+            const int c = col / (d->S * d->R);
+            if (c < 0 || c >= Cg) return -2;
+            off[j] = (r * Wp + s) * d->C + g * Cg + c;
+        }
+    }
+    return 0;
+}
+
 static float *padded_copy(const oracle_desc *d, const float *img)
 {
     const int Hp = d->H + 2 * d->pad, Wp = d->W + 2 * d->pad;
@@ -112,10 +139,14 @@ static float *padded_copy(const oracle_desc *d, const float *img)
 }
 
 /*
- * Parity variant.  Figure 2's loop nest with every product formed exactly in
- * fp64 from the two fp32 operands and accumulated in fp64.
- * out[n][k][y][x] receives the sum, absum[n][k][y][x] the sum of |products|
- * (the scale of the comparison tolerance).  Either may be NULL.
+ * Parity variant.  For every image and output channel, each stored weight
+ * slides over the padded image of its input channel (the loop nest of
+ * Figure 2): the weight's pre-lowered offset names the top-left corner of
+ * the window it multiplies, output pixel (oy, ox) reads the element
+ * oy*stride rows and ox*stride columns further.  Every product is formed
+ * exactly in fp64 from the two fp32 operands and summed in fp64.
+ * out[n][k][oy][ox] receives the sum, absum[n][k][oy][ox] the sum of
+ * |products| (the scale of the comparison tolerance).  Either may be NULL.
  */
 int oracle_forward_f64(const oracle_desc *d, int32_t N, const int32_t *rowptr,
                        const int32_t *off, const float *val, const float *in,
@@ -124,41 +155,44 @@ int oracle_forward_f64(const oracle_desc *d, int32_t N, const int32_t *rowptr,
     if (!desc_ok(d) || N < 1 || !rowptr || !in) return -1;
     const int Wp = d->W + 2 * d->pad;
     const int OH = oracle_out_h(d), OW = oracle_out_w(d);
-    const size_t img = (size_t)d->C * d->H * d->W;
+    const size_t plane = (size_t)OH * OW;
+    const size_t image_floats = (size_t)d->C * d->H * d->W;
     int fail = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < N; ++n) {
-        float *ip = padded_copy(d, in + (size_t)n * img);
-        double *acc = (double *)malloc(sizeof(double) * 2 * OH * OW);
-        if (!ip || !acc) { fail = 1; free(ip); free(acc); continue; }
-        double *ab = acc + (size_t)OH * OW;
+        float *padded = padded_copy(d, in + (size_t)n * image_floats);
+        double *sum = (double *)malloc(sizeof(double) * 2 * plane);
+        if (!padded || !sum) { fail = 1; free(padded); free(sum); continue; }
+        double *mag = sum + plane;
         for (int k = 0; k < d->K; ++k) {
-            for (int i = 0; i < 2 * OH * OW; ++i) acc[i] = 0.0;
-            for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
-                const int32_t o = off[j];
-                const double coeff = (double)val[j];
-                for (int y = 0; y < OH; ++y) {
-                    for (int x = 0; x < OW; ++x) {
-                        const double p = coeff * (double)ip[o + y * d->stride * Wp + x * d->stride];
-                        acc[y * OW + x] += p;
-                        ab[y * OW + x] += fabs(p);
+            for (size_t i = 0; i < 2 * plane; ++i) sum[i] = 0.0;
+            for (int32_t e = rowptr[k]; e < rowptr[k + 1]; ++e) {
+                const float *window = padded + off[e];
+                const double weight = (double)val[e];
+                for (int oy = 0; oy < OH; ++oy) {
+                    const float *line = window + (size_t)oy * d->stride * Wp;
+                    for (int ox = 0; ox < OW; ++ox) {
+                        const double prod = weight * (double)line[ox * d->stride];
+                        sum[oy * OW + ox] += prod;
+                        mag[oy * OW + ox] += fabs(prod);
                     }
                 }
             }
-            const size_t base = ((size_t)n * d->K + k) * OH * OW;
-            if (out) memcpy(out + base, acc, sizeof(double) * OH * OW);
-            if (absum) memcpy(absum + base, ab, sizeof(double) * OH * OW);
+            const size_t base = ((size_t)n * d->K + k) * plane;
+            if (out) memcpy(out + base, sum, sizeof(double) * plane);
+            if (absum) memcpy(absum + base, mag, sizeof(double) * plane);
         }
-        free(ip);
-        free(acc);
+        free(padded);
+        free(sum);
     }
     return fail ? -3 : 0;
 }
 
 /*
- * Timed variant: Figure 2 as written, fp32 multiply-add in CSR order, images
- * and output channels spread over `nthreads` OpenMP threads (<= 0: all).
- * Returns the number of threads used, or a negative error.
+ * Timed variant: the same walk (image, output channel, stored weight,
+ * output pixel) with fp32 multiply-adds in CSR order, the
+ * (image, output channel) pairs spread over `nthreads` OpenMP threads
+ * (<= 0: all).  Returns the number of threads used, or a negative error.
  */
 int oracle_forward_f32(const oracle_desc *d, int32_t N, const int32_t *rowptr,
                        const int32_t *off, const float *val, const float *in,
@@ -167,9 +201,10 @@ int oracle_forward_f32(const oracle_desc *d, int32_t N, const int32_t *rowptr,
     if (!desc_ok(d) || N < 1 || !rowptr || !in || !out) return -1;
     const int Wp = d->W + 2 * d->pad;
     const int OH = oracle_out_h(d), OW = oracle_out_w(d);
-    const size_t img = (size_t)d->C * d->H * d->W;
-    float **ip = (float **)calloc((size_t)N, sizeof(float *));
-    if (!ip) return -3;
+    const size_t plane = (size_t)OH * OW;
+    const size_t image_floats = (size_t)d->C * d->H * d->W;
+    float **padded = (float **)calloc((size_t)N, sizeof(float *));
+    if (!padded) return -3;
     int used = 1, fail = 0;
 #ifdef _OPENMP
     if (nthreads > 0) omp_set_num_threads(nthreads);
@@ -182,26 +217,29 @@ int oracle_forward_f32(const oracle_desc *d, int32_t N, const int32_t *rowptr,
 #endif
 #pragma omp for schedule(static)
         for (int n = 0; n < N; ++n) {
-            ip[n] = padded_copy(d, in + (size_t)n * img);
-            if (!ip[n]) fail = 1;
+            padded[n] = padded_copy(d, in + (size_t)n * image_floats);
+            if (!padded[n]) fail = 1;
         }
-#pragma omp for collapse(2) schedule(static)
-        for (int n = 0; n < N; ++n) {
-            for (int k = 0; k < d->K; ++k) {
-                if (fail) continue;
-                float *o = out + ((size_t)n * d->K + k) * OH * OW;
-                for (int i = 0; i < OH * OW; ++i) o[i] = 0.0f;
-                for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
-                    const float *src = ip[n] + off[j];
-                    const float coeff = val[j];
-                    for (int y = 0; y < OH; ++y)
-                        for (int x = 0; x < OW; ++x)
-                            o[y * OW + x] += coeff * src[y * d->stride * Wp + x * d->stride];
+        /* one work item per (image, output channel); the channel's group is implied by its offsets */
+#pragma omp for schedule(static)
+        for (long item = 0; item < (long)N * d->K; ++item) {
+            if (fail) continue;
+            const int n = (int)(item / d->K);
+            const int k = (int)(item % d->K);
+            float *res = out + ((size_t)n * d->K + k) * plane;
+            for (size_t i = 0; i < plane; ++i) res[i] = 0.0f;
+            for (int32_t e = rowptr[k]; e < rowptr[k + 1]; ++e) {
+                const float *window = padded[n] + off[e];
+                const float weight = val[e];
+                for (int oy = 0; oy < OH; ++oy) {
+                    const float *line = window + (size_t)oy * d->stride * Wp;
+                    float *dst = res + (size_t)oy * OW;
+                    for (int ox = 0; ox < OW; ++ox) dst[ox] += weight * line[ox * d->stride];
                 }
             }
         }
     }
-    for (int n = 0; n < N; ++n) free(ip[n]);
-    free(ip);
+    for (int n = 0; n < N; ++n) free(padded[n]);
+    free(padded);
     return fail ? -3 : used;
 }

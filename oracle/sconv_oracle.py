@@ -38,6 +38,8 @@ def _load():
         L.oracle_csr_from_dense.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_lower_offsets.restype = C.c_int
         L.oracle_lower_offsets.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_lower_offsets_hwc.restype = C.c_int
+        L.oracle_lower_offsets_hwc.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_forward_f64.restype = C.c_int
         L.oracle_forward_f64.argtypes = [C.POINTER(Desc), C.c_int32] + [C.c_void_p] * 6
         L.oracle_forward_f32.restype = C.c_int
@@ -86,6 +88,17 @@ def lower_offsets(layer, rowptr, colidx):
     rc = L.oracle_lower_offsets(C.byref(d), _p(rowptr), _p(colidx), _p(off))
     if rc:
         raise ValueError(f"oracle_lower_offsets failed: {rc}")
+    return off
+
+
+def lower_offsets_hwc(layer, rowptr, colidx):
+    """Column indices -> offsets into the zero-padded HWC image (channel innermost)."""
+    L = _load()
+    d = _desc(layer)
+    off = np.zeros(len(colidx), dtype=np.int32)
+    rc = L.oracle_lower_offsets_hwc(C.byref(d), _p(rowptr), _p(colidx), _p(off))
+    if rc:
+        raise ValueError(f"oracle_lower_offsets_hwc failed: {rc}")
     return off
 
 

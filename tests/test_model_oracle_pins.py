@@ -97,3 +97,46 @@ def test_gsl_rules_on_the_papers_examples():
     order = {"stop": 0, "prune": 1, "restore_dense": 2}
     seq = [order[pm.gsl_decide(CONV5, 1, x, True, F, B, a)] for x in (0.005, 0.01, 0.03, 0.1, 0.3, 0.34, 0.6, 1.0)]
     assert seq == sorted(seq) and seq[0] == 0 and seq[-1] == 2
+
+
+# ------------------------------------------------------------ the "lowered" curve of the Section 2.2 figure
+def test_lowered_counts_closed_form():
+    """Lowering turns the C x H x W input into a (C*R*S) x (OH*OW) matrix: for conv5 (3x3, stride 1, pad 1)
+    every input element appears 9 times."""
+    flops, s_a, s_w = pm.layer_counts(CONV5, 1, lowered=True)
+    d_flops, d_s_a, d_s_w = pm.layer_counts(CONV5, 1)
+    assert (flops, s_w) == (d_flops, d_s_w)                 # the arithmetic and the weights do not change
+    assert s_a == 4 * (384 * 9 * 169 + 256 * 169)
+    conv1 = wl.LAYERS["conv1"]                              # strided: 121 taps, 55 x 55 windows
+    assert pm.layer_counts(conv1, 2, lowered=True)[1] == 4 * 2 * (3 * 121 * 55 * 55 + 96 * 55 * 55)
+
+
+@pytest.mark.parametrize("plat", ["bdw", "atom"])
+def test_lowered_curve_saturates_at_a_higher_density_than_direct(plat):
+    """What the figure shows for conv5: both curves coincide while compute bound; the lowered one turns
+    bandwidth bound at a higher density and its plateau is lower by the ratio of the activation bytes."""
+    F, B, a = GOLD[f"{plat}_sgemm_gflops"] * 1e9, GOLD[f"{plat}_bw_gbs"] * 1e9, GOLD[f"{plat}_alpha"]
+    direct = pm.predict(CONV5, 1, 0.2, F, B, a)
+    lowered = pm.predict(CONV5, 1, 0.2, F, B, a, lowered=True)
+    assert lowered["x_upper"] > 3 * direct["x_upper"]
+    assert lowered["x_lower"] == direct["x_lower"]
+    x_hi = 1.5 * lowered["x_upper"]                         # both compute bound
+    assert pm.predict(CONV5, 1, x_hi, F, B, a, lowered=True)["speedup"] == pm.predict(CONV5, 1, x_hi, F, B, a)["speedup"]
+    x_lo = 0.5 * direct["x_upper"]                          # both bandwidth bound
+    pd, pl = pm.predict(CONV5, 1, x_lo, F, B, a), pm.predict(CONV5, 1, x_lo, F, B, a, lowered=True)
+    assert pd["bandwidth_bound"] and pl["bandwidth_bound"] and pl["speedup"] < pd["speedup"]
+    beta = 2.0
+    want = (pd["bytes_act"] + beta * x_lo * pd["bytes_w"]) / (pl["bytes_act"] + beta * x_lo * pl["bytes_w"])
+    assert math.isclose(pl["speedup"] / pd["speedup"], want, rel_tol=1e-12)
+    # direct convolution keeps its advantage over the whole "typical" range only where lowering is bandwidth bound
+    for x in (0.05, 0.1, 0.15):
+        assert pm.predict(CONV5, 1, x, F, B, a, lowered=True)["speedup"] <= pm.predict(CONV5, 1, x, F, B, a)["speedup"]
+
+
+def test_fixed_time_only_shifts_the_sparse_time():
+    F, B, a = GOLD["bdw_sgemm_gflops"] * 1e9, GOLD["bdw_bw_gbs"] * 1e9, GOLD["bdw_alpha"]
+    p0 = pm.predict(CONV5, 8, 0.1, F, B, a)
+    p1 = pm.predict(CONV5, 8, 0.1, F, B, a, t_fixed=5e-6)
+    assert p1["t_sparse"] == p0["t_sparse"] + 5e-6 and p1["t_dense"] == p0["t_dense"]
+    assert p1["x_upper"] == p0["x_upper"] and p1["x_lower"] == p0["x_lower"]
+    assert math.isclose(p1["speedup"], p0["t_dense"] / (p0["t_sparse"] + 5e-6), rel_tol=1e-15)

@@ -206,6 +206,40 @@ def test_lowered_offsets_closed_form_and_additivity(oracle, dims):
         assert np.all(np.diff(seg) > 0)
 
 
+@pytest.mark.parametrize("dims", TINY)
+def test_hwc_offsets_name_the_same_elements_as_chw(oracle, dims):
+    """The channel-innermost layout function: for every stored weight and every output position, the
+    element the HWC offset reaches in the padded HWC image is the element the CHW offset reaches in the
+    padded CHW image (the images hold distinct numbers, so equal values mean the same element); and a
+    convolution gathered through the HWC offsets equals the oracle's result bit for bit."""
+    layer = wl.small_layer(**dims)
+    x, w = rand_case(layer, 1, 0.5, seed=29)
+    rowptr, colidx, val = oracle.csr_from_dense(layer, w)
+    off = oracle.lower_offsets(layer, rowptr, colidx)
+    off_h = oracle.lower_offsets_hwc(layer, rowptr, colidx)
+    Hp, Wp, C, st = layer.H + 2 * layer.pad, layer.W + 2 * layer.pad, layer.C, layer.stride
+    # closed form
+    nz = np.argwhere(w != 0)
+    for j, (k, c, r, s) in enumerate(nz):
+        assert off_h[j] == (r * Wp + s) * C + (k // layer.Kg) * layer.Cg + c
+    ident = np.arange(1, C * Hp * Wp + 1, dtype=np.int64).reshape(C, Hp, Wp)
+    chw, hwc = ident.ravel(), ident.transpose(1, 2, 0).ravel()
+    ys, xs = np.meshgrid(np.arange(layer.OH), np.arange(layer.OW), indexing="ij")
+    shift = (ys * st * Wp + xs * st).ravel()
+    assert (off[:, None] + shift[None, :]).max() < C * Hp * Wp and (off_h[:, None] + shift[None, :] * C).max() < C * Hp * Wp
+    assert np.array_equal(chw[off[:, None] + shift[None, :]], hwc[off_h[:, None] + shift[None, :] * C])
+    # and the convolution itself, gathered from the padded HWC image in CSR order
+    ref, _ = oracle.forward_f64(layer, rowptr, off, val, x)
+    xp = np.zeros((C, Hp, Wp), dtype=np.float32)
+    xp[:, layer.pad:layer.pad + layer.H, layer.pad:layer.pad + layer.W] = x[0]
+    img = xp.transpose(1, 2, 0).ravel().astype(np.float64)
+    got = np.zeros((layer.K, layer.OH * layer.OW))
+    for k in range(layer.K):
+        for j in range(rowptr[k], rowptr[k + 1]):
+            got[k] += np.float64(val[j]) * img[off_h[j] + shift * C]
+    assert np.array_equal(got.reshape(ref.shape[1:]), ref[0])
+
+
 # ------------------------------------------------------------ timed fp32 variant
 def test_fp32_variant_agrees_with_fp64(oracle):
     layer = wl.small_layer(C=16, H=13, W=13, K=24, R=3, S=3, stride=1, pad=1, groups=2)

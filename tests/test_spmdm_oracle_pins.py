@@ -73,3 +73,23 @@ def test_bias_relu_rows():
     assert np.allclose(scale, ab + np.abs(bias)[:, None])
     res2, scale2 = so.bias_relu_t(out, ab, None, False)
     assert np.array_equal(res2, out) and np.array_equal(scale2, ab)
+
+
+def test_fully_connected_layer_with_bias_and_relu_is_torchs_linear():
+    """The whole fully connected oracle (product, bias per output feature, ReLU) against the library's own
+    fp64 layer: torch.nn.functional.linear takes image-major activations [N][C] and returns [N][K]."""
+    import torch
+
+    w, x_t = case(9, 14, 6, 0.4, 6)
+    bias = np.linspace(-0.3, 0.3, 9).astype(np.float32)
+    out, ab = so.spmdm(w, x_t)
+    res, _ = so.bias_relu_t(out, ab, bias, True)
+    lin = torch.nn.functional.linear(torch.from_numpy(x_t.T.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                     torch.from_numpy(bias.astype(np.float64)))
+    want = torch.relu(lin).numpy().T
+    assert (want == 0).any() and (want > 0).any()
+    assert np.allclose(res, want, rtol=1e-13, atol=1e-15)
+    # a bias on the wrong axis, or a ReLU before the bias, does not survive this
+    assert not np.allclose(np.maximum(out, 0) + bias[:, None], want)
+    res_nb, _ = so.bias_relu_t(out, ab, None, True)
+    assert np.allclose(res_nb, torch.relu(lin - torch.from_numpy(bias.astype(np.float64))).numpy().T, rtol=1e-13, atol=1e-15)
