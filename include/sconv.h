@@ -16,8 +16,9 @@
  * No im2col buffer and no dense weight matrix is ever formed.
  *
  * All functions return 0 (SCONV_OK) or a negative sconv_status; they never
- * throw and keep no global state.  Distinct handles may be used from distinct
- * threads.  Pointers marked [host] are read or written on the CPU during the
+ * throw.  Apart from a mutex-guarded record of which kernels have been enabled
+ * for large LDS on which device, all state lives in the handles: distinct
+ * handles may be used from distinct threads.  Pointers marked [host] are read or written on the CPU during the
  * call; pointers marked [device] are HIP device addresses that must stay valid
  * until the stream work enqueued by the call has finished.
  */
@@ -94,6 +95,24 @@ int sconv_create_csr(const sconv_desc *desc, const float *dense_w, const sconv_p
 int sconv_create_csr_from_arrays(const sconv_desc *desc, const int32_t *rowptr, const int32_t *colidx,
                                  const float *values, const sconv_plan *plan, sconv_csr **out);
 
+/*
+ * The lowering step alone, for either of two layouts of the zero-padded input
+ * image (Section 2.1: the method needs only a layout function f with
+ * f(c, y+r, x+s) = f(c, y, x) + f(0, r, s)):
+ *   SCONV_LAYOUT_CHW  f(c,y,x) = (c*Hp + y)*Wp + x   (Figure 2's example; what the kernels read)
+ *   SCONV_LAYOUT_HWC  f(c,y,x) = (y*Wp + x)*C + c    (channel innermost)
+ * rowptr / colidx [host] as for sconv_create_csr_from_arrays; off[nnz] [host]
+ * receives f(g*Cg + c, r, s) per nonzero, in CSR order.  *step_y and *step_x
+ * (may be NULL) receive f(0, stride, 0) and f(0, 0, stride): output (y, x) reads
+ * in_pad[off + y * step_y + x * step_x].  Host arithmetic only.  The device
+ * entry points take CHW inputs; an HWC tensor has to be run through a loop of
+ * the caller's own, which is what this function prepares.  SCONV_ERR_DESC for
+ * an unknown layout.
+ */
+typedef enum { SCONV_LAYOUT_CHW = 0, SCONV_LAYOUT_HWC = 1 } sconv_layout;
+int sconv_lower_offsets(const sconv_desc *desc, int32_t layout, const int32_t *rowptr, const int32_t *colidx,
+                        int32_t *off, int32_t *step_y, int32_t *step_x);
+
 /* Sizes and the tiling in use.  Any output pointer may be NULL. */
 int sconv_csr_info(const sconv_csr *h, int64_t *nnz, int32_t *out_h, int32_t *out_w, sconv_plan *plan);
 
@@ -123,8 +142,10 @@ int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t
  * (a hipStream_t; NULL = the default stream) of the current device and not
  * waited for.  `in` and `out` must not overlap.  A tiling the library chose
  * itself follows N: the first call with a new batch size chooses and packs for
- * it (host work, milliseconds, and an upload); the packings of the last four
+ * it (host work, milliseconds, then a device allocation and a blocking upload:
+ * that call synchronises with the device); the packings of the last four
  * tilings stay on the device, so alternating batch sizes cost nothing more.
+ * If packing for a new N fails the handle keeps the packing it had.
  * Calls on one handle must not overlap in time (the handle owns scratch);
  * different handles are independent.
  */
@@ -222,6 +243,9 @@ typedef struct {
     double lane_efficiency;   /* fraction of that ceiling the kernel sustains as useful multiply-adds
                                  (lanes that are real outputs x issue slots not lost to address
                                  arithmetic, waits and barriers) */
+    double t_fixed;           /* seconds per call outside the paper's model (launch, prologue, first
+                                 block, last stores), added to the sparse time; 0 = the formulas as
+                                 Section 2.2 prints them */
 } sconv_machine;
 
 typedef struct {
@@ -233,7 +257,7 @@ typedef struct {
     double t_dense;           /* C/F, seconds */
     double t_sparse_compute;  /* alpha*x*C/F */
     double t_sparse_bw;       /* (S_A + beta*x*S_W)/B */
-    double t_sparse;          /* max of the two */
+    double t_sparse;          /* max of the two (+ the machine's t_fixed) */
     double speedup;           /* t_dense / t_sparse */
     double effective_flops;   /* C / t_sparse (zeros counted) */
     double actual_flops;      /* x*C / t_sparse (nonzeros only) */
@@ -242,7 +266,7 @@ typedef struct {
     int32_t bandwidth_bound;  /* 1 if t_sparse_bw > t_sparse_compute */
 } sconv_prediction;
 
-/* Measured defaults for one MI355X. */
+/* Measured defaults for one MI355X (t_fixed included: set it to 0 for the paper's formulas alone). */
 void sconv_machine_gfx950(sconv_machine *m);
 
 /*
@@ -252,6 +276,17 @@ void sconv_machine_gfx950(sconv_machine *m);
  */
 int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
                         const sconv_machine *m, sconv_prediction *out);
+
+/*
+ * The same model for sparse convolution on LOWERED tensors, the curve the
+ * figure of Section 2.2 draws beside the direct one: lowering replicates the
+ * input (Section 2.1), so S_A becomes 4*N*(C*R*S*OH*OW + K*OH*OW), the lowered
+ * matrix plus the output; everything else is unchanged.  The cost of creating
+ * the lowered matrix is not charged.  Only the model: no lowering-based kernel
+ * is part of this library.
+ */
+int sconv_model_predict_lowered(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
+                                const sconv_machine *m, sconv_prediction *out);
 
 /*
  * How evenly the packing spreads the nonzeros (the load-balance step of the
@@ -275,11 +310,12 @@ int sconv_csr_balance(const sconv_csr *h, sconv_balance *out);
 /* ---- the pruning controller's decision (Section 2.3, the Guided Sparsity Learning algorithm) ---- */
 
 /*
- * What the algorithm does with one layer, given the model.  Sparsity bounds are
- * stated as densities here: the "upper bound of the useful sparsity range" is
- * the density x_upper below which the layer is bandwidth bound and pruning
- * brings no more speed; the "lower bound" is the density x_lower = 1/alpha
- * above which the sparse kernel is slower than dense convolution.
+ * What the algorithm does with one layer, given the model.  The algorithm's two
+ * sparsity bounds are stated as densities here: x_upper is the density below
+ * which the layer is bandwidth bound and pruning brings no more speed (the
+ * algorithm's upper sparsity bound); x_lower = 1/alpha is the density above
+ * which the sparse kernel is slower than dense convolution (its lower sparsity
+ * bound).
  */
 typedef enum {
     SCONV_GSL_EXCLUDE = 0,        /* no useful range (x_upper >= x_lower): never prune this layer */

@@ -29,7 +29,7 @@ class sconv_plan(C.Structure):
 
 class sconv_machine(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("dense_flops", "hbm_bytes_per_s", "alpha", "beta", "fma_flops",
-                                          "lds_bytes_per_s", "lds_bytes_per_fma", "lane_efficiency")]
+                                          "lds_bytes_per_s", "lds_bytes_per_fma", "lane_efficiency", "t_fixed")]
 
 
 class sconv_prediction(C.Structure):
@@ -50,7 +50,9 @@ class sconv_balance(C.Structure):
 EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info", "sconv_csr_export",
            "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
            "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance",
-           "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune", "sconv_rank_plans"]
+           "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune", "sconv_rank_plans",
+           "sconv_lower_offsets", "sconv_model_predict_lowered"]
+LAYOUT_CHW, LAYOUT_HWC = 0, 1
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
 
@@ -89,6 +91,8 @@ def lib():
         L.sconv_machine_gfx950.restype = None
         L.sconv_model_predict.argtypes = [C.POINTER(sconv_desc), i32, C.c_double, vp, C.POINTER(sconv_machine),
                                           C.POINTER(sconv_prediction)]
+        L.sconv_model_predict_lowered.argtypes = L.sconv_model_predict.argtypes
+        L.sconv_lower_offsets.argtypes = [C.POINTER(sconv_desc), i32, vp, vp, vp, C.POINTER(i32), C.POINTER(i32)]
         L.sconv_gsl_decide.argtypes = [C.POINTER(sconv_desc), i32, C.c_double, i32, C.POINTER(sconv_machine),
                                        C.POINTER(i32), C.POINTER(sconv_prediction)]
         L.sconv_csr_balance.argtypes = [C.c_void_p, C.POINTER(sconv_balance)]
@@ -193,8 +197,8 @@ def sconv_csr_unpack(csr: Csr, which: int):
     return _export(lib().sconv_csr_unpack, csr, C.c_int32(which))
 
 
-def sconv_forward(csr: Csr, x, out=None, stream=None):
-    """x: contiguous fp32 CUDA tensor [N,C,H,W]; returns/overwrites out [N,K,OH,OW] on the same device."""
+def _conv_buffers(csr: Csr, x, out, stream):
+    """Checks the input tensor, allocates or checks the output, picks the stream: (N, out, stream)."""
     import torch
 
     assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
@@ -206,7 +210,34 @@ def sconv_forward(csr: Csr, x, out=None, stream=None):
         out = torch.empty((N, L.K, info["OH"], info["OW"]), dtype=torch.float32, device=x.device)
     assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
     assert tuple(out.shape) == (N, L.K, info["OH"], info["OW"])
-    s = stream if stream is not None else torch.cuda.current_stream(x.device)
+    return N, out, stream if stream is not None else torch.cuda.current_stream(x.device)
+
+
+def _fc_buffers(csr: Csr, x_t, out_t, bias, stream):
+    import torch
+
+    L = csr.layer
+    assert x_t.is_cuda and x_t.dtype == torch.float32 and x_t.is_contiguous() and x_t.dim() == 2 and x_t.shape[0] == L.C
+    N = x_t.shape[1]
+    if out_t is None:
+        out_t = torch.empty((L.K, N), dtype=torch.float32, device=x_t.device)
+    assert out_t.is_cuda and out_t.dtype == torch.float32 and out_t.is_contiguous() and tuple(out_t.shape) == (L.K, N)
+    _check_bias(csr, bias)
+    return N, out_t, stream if stream is not None else torch.cuda.current_stream(x_t.device)
+
+
+def _check_bias(csr: Csr, bias):
+    import torch
+
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and tuple(bias.shape) == (csr.layer.K,)
+
+
+def sconv_forward(csr: Csr, x, out=None, stream=None):
+    """x: contiguous fp32 CUDA tensor [N,C,H,W]; returns/overwrites out [N,K,OH,OW] on the same device."""
+    import torch
+
+    N, out, s = _conv_buffers(csr, x, out, stream)
     with torch.cuda.device(x.device):
         rc = lib().sconv_forward(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N,
                                  C.c_void_p(s.cuda_stream))
@@ -228,16 +259,7 @@ def sconv_tune(csr: Csr, x, out=None, max_plans=8, stream=None):
     """Times the best-ranked tilings for this batch size on x and keeps the fastest; returns the output."""
     import torch
 
-    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
-    L = csr.layer
-    assert tuple(x.shape[1:]) == (L.C, L.H, L.W), (tuple(x.shape), L)
-    N = x.shape[0]
-    info = sconv_csr_info(csr)
-    if out is None:
-        out = torch.empty((N, L.K, info["OH"], info["OW"]), dtype=torch.float32, device=x.device)
-    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
-    assert tuple(out.shape) == (N, L.K, info["OH"], info["OW"])
-    s = stream if stream is not None else torch.cuda.current_stream(x.device)
+    N, out, s = _conv_buffers(csr, x, out, stream)
     with torch.cuda.device(x.device):
         rc = lib().sconv_tune(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N, int(max_plans),
                               C.c_void_p(s.cuda_stream))
@@ -251,18 +273,8 @@ def sconv_forward_fused(csr: Csr, x, bias=None, relu=False, out=None, stream=Non
     tensor [K] or None."""
     import torch
 
-    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
-    L = csr.layer
-    assert tuple(x.shape[1:]) == (L.C, L.H, L.W), (tuple(x.shape), L)
-    N = x.shape[0]
-    info = sconv_csr_info(csr)
-    if out is None:
-        out = torch.empty((N, L.K, info["OH"], info["OW"]), dtype=torch.float32, device=x.device)
-    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
-    assert tuple(out.shape) == (N, L.K, info["OH"], info["OW"])
-    if bias is not None:
-        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and tuple(bias.shape) == (L.K,)
-    s = stream if stream is not None else torch.cuda.current_stream(x.device)
+    N, out, s = _conv_buffers(csr, x, out, stream)
+    _check_bias(csr, bias)
     with torch.cuda.device(x.device):
         rc = lib().sconv_forward_fused(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N,
                                        C.c_void_p(bias.data_ptr()) if bias is not None else None, int(bool(relu)),
@@ -288,15 +300,7 @@ def sconv_fc_forward(csr: Csr, x_t, bias=None, relu=False, out_t=None, stream=No
     """x_t: contiguous fp32 CUDA tensor [C][N] (feature-major); returns/overwrites out_t [K][N]."""
     import torch
 
-    L = csr.layer
-    assert x_t.is_cuda and x_t.dtype == torch.float32 and x_t.is_contiguous() and x_t.dim() == 2 and x_t.shape[0] == L.C
-    N = x_t.shape[1]
-    if out_t is None:
-        out_t = torch.empty((L.K, N), dtype=torch.float32, device=x_t.device)
-    assert out_t.is_cuda and out_t.dtype == torch.float32 and out_t.is_contiguous() and tuple(out_t.shape) == (L.K, N)
-    if bias is not None:
-        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and tuple(bias.shape) == (L.K,)
-    s = stream if stream is not None else torch.cuda.current_stream(x_t.device)
+    N, out_t, s = _fc_buffers(csr, x_t, out_t, bias, stream)
     with torch.cuda.device(x_t.device):
         rc = lib().sconv_fc_forward(csr.handle, C.c_void_p(x_t.data_ptr()), C.c_void_p(out_t.data_ptr()), N,
                                     C.c_void_p(bias.data_ptr()) if bias is not None else None, int(bool(relu)),
@@ -310,13 +314,7 @@ def sconv_fc_tune(csr: Csr, x_t, out_t=None, max_plans=8, stream=None):
     """Times the best-ranked tilings of the fully connected layer for this batch size; returns the output."""
     import torch
 
-    L = csr.layer
-    assert x_t.is_cuda and x_t.dtype == torch.float32 and x_t.is_contiguous() and x_t.dim() == 2 and x_t.shape[0] == L.C
-    N = x_t.shape[1]
-    if out_t is None:
-        out_t = torch.empty((L.K, N), dtype=torch.float32, device=x_t.device)
-    assert out_t.is_cuda and out_t.dtype == torch.float32 and out_t.is_contiguous() and tuple(out_t.shape) == (L.K, N)
-    s = stream if stream is not None else torch.cuda.current_stream(x_t.device)
+    N, out_t, s = _fc_buffers(csr, x_t, out_t, None, stream)
     with torch.cuda.device(x_t.device):
         rc = lib().sconv_fc_tune(csr.handle, C.c_void_p(x_t.data_ptr()), C.c_void_p(out_t.data_ptr()), N, int(max_plans),
                                  C.c_void_p(s.cuda_stream))
@@ -338,6 +336,27 @@ def sconv_model_predict(layer, N: int, density: float, csr: Csr | None = None, m
                                      C.byref(machine) if machine is not None else None, C.byref(p)),
            "sconv_model_predict")
     return p.as_dict()
+
+
+def sconv_model_predict_lowered(layer, N: int, density: float, csr: Csr | None = None, machine: sconv_machine | None = None):
+    d = make_desc(layer)
+    p = sconv_prediction()
+    _check(lib().sconv_model_predict_lowered(C.byref(d), N, float(density), csr.handle if csr else None,
+                                             C.byref(machine) if machine is not None else None, C.byref(p)),
+           "sconv_model_predict_lowered")
+    return p.as_dict()
+
+
+def sconv_lower_offsets(layer, layout: int, rowptr, colidx):
+    """(off int32[nnz], step_y, step_x) for a padded image stored in `layout` (LAYOUT_CHW or LAYOUT_HWC)."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    d = make_desc(layer)
+    off = np.zeros(max(len(colidx), 1), dtype=np.int32)
+    sy, sx = C.c_int32(), C.c_int32()
+    _check(lib().sconv_lower_offsets(C.byref(d), int(layout), _np_ptr(rowptr), _np_ptr(colidx), _np_ptr(off),
+                                     C.byref(sy), C.byref(sx)), "sconv_lower_offsets")
+    return off[:len(colidx)], sy.value, sx.value
 
 
 def sconv_csr_balance(h) -> dict:

@@ -29,12 +29,13 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    build_ceilings(hipcc)
     return LIB
 
 
-def build_ceilings(hipcc: str) -> str:
-    """The ceilings microbenchmark (stand-alone program, see csrc/sconv_ceilings.hip)."""
+def build_ceilings(hipcc: str | None = None) -> str:
+    """The ceilings microbenchmark (stand-alone program, see csrc/sconv_ceilings.hip); only the profiling
+    runs use it, so it is built on request: python -m paper_1608_01409_amd.build --ceilings"""
+    hipcc = hipcc or os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_ceilings.py")])
     exe = os.path.join(HERE, "sconv_ceilings")
     cmd = [hipcc, "-O3", "-std=c++17", *DEVICE_FLAGS, "-I", CSRC, os.path.join(CSRC, "sconv_ceilings.hip"), "-o", exe]
@@ -46,3 +47,5 @@ def build_ceilings(hipcc: str) -> str:
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    if "--ceilings" in sys.argv[1:]:
+        print(build_ceilings())

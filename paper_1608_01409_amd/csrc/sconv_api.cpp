@@ -108,7 +108,10 @@ static bool same_plan(const sconv_plan &a, const sconv_plan &b)
 }
 
 // Choose (or re-choose) the LDS tiling for batch size n and pack for it.  The best tiling depends on the
-// batch: with few image tiles smaller workgroups are needed to occupy every CU.
+// batch: with few image tiles smaller workgroups are needed to occupy every CU.  The handle changes only
+// once the new packing exists: after an error it still holds, and runs, the packing it had.
+static const size_t kPlansRemembered = 64; // batch sizes whose tiling is kept; beyond that the table starts over
+
 static int plan_lds(sconv_csr *h, int n)
 {
     const sconv_desc &d = h->kdesc;
@@ -116,16 +119,35 @@ static int plan_lds(sconv_csr *h, int n)
     LdsTiling t;
     int rc;
     auto known = h->plan_of_n.find(n);
-    if (known != h->plan_of_n.end()) {
-        rc = make_lds_tiling(d, known->second, n, avg, t); // every field given: no search
-    } else {
-        rc = make_lds_tiling(d, h->requested, n, avg, t);
-        if (!rc) h->plan_of_n[n] = t.p;
-    }
+    const bool fresh = known == h->plan_of_n.end();
+    rc = make_lds_tiling(d, fresh ? h->requested : known->second, n, avg, t); // a known tiling has every field: no search
     if (rc) return rc;
-    h->planned_n = n;
-    if (h->has_lds && same_plan(t.p, h->flat ? h->lds_flat.t.p : h->lds.t.p)) return SCONV_OK;
-    if (h->has_lds) { // set the current packing aside, device copies and all
+    auto remember = [&]() {
+        if (!fresh) return;
+        if (h->plan_of_n.size() >= kPlansRemembered) h->plan_of_n.clear();
+        h->plan_of_n[n] = t.p;
+    };
+    if (h->has_lds && same_plan(t.p, h->flat ? h->lds_flat.t.p : h->lds.t.p)) {
+        remember();
+        h->planned_n = n;
+        return SCONV_OK;
+    }
+    // an earlier packing for this tiling, device copies and all?
+    size_t found = h->stash.size();
+    for (size_t i = 0; i < h->stash.size(); ++i) {
+        const StashedPacking &sp = h->stash[i];
+        if (same_plan(t.p, sp.flat ? sp.lds_flat.t.p : sp.lds.t.p)) found = i;
+    }
+    StashedPacking next;
+    if (found < h->stash.size()) {
+        next = std::move(h->stash[found]);
+        h->stash.erase(h->stash.begin() + (long)found);
+    } else {
+        next.flat = t.p.kernel == 3;
+        rc = next.flat ? pack_flat(d, h->kc(), t, next.lds_flat) : pack_lds(d, h->kc(), t, next.lds);
+        if (rc) return rc;
+    }
+    if (h->has_lds) { // set the current packing aside
         StashedPacking old;
         old.flat = h->flat;
         old.lds = std::move(h->lds);
@@ -133,30 +155,19 @@ static int plan_lds(sconv_csr *h, int n)
         old.dev = h->dev_lds;
         old.uploaded = h->lds_uploaded;
         h->stash.push_back(std::move(old));
-        h->dev_lds = DeviceLds();
-        h->lds_uploaded = false;
-        h->has_lds = false;
         while (h->stash.size() > h->stash_cap) { // hipFree waits for launches that still read the arrays
             release_arrays(h->stash.front().dev);
             h->stash.erase(h->stash.begin());
         }
     }
-    for (size_t i = 0; i < h->stash.size(); ++i) {
-        StashedPacking &sp = h->stash[i];
-        if (!same_plan(t.p, sp.flat ? sp.lds_flat.t.p : sp.lds.t.p)) continue;
-        h->flat = sp.flat;
-        h->lds = std::move(sp.lds);
-        h->lds_flat = std::move(sp.lds_flat);
-        h->dev_lds = sp.dev;
-        h->lds_uploaded = sp.uploaded;
-        h->has_lds = true;
-        h->stash.erase(h->stash.begin() + (long)i);
-        return SCONV_OK;
-    }
-    h->flat = t.p.kernel == 3;
-    rc = h->flat ? pack_flat(d, h->kc(), t, h->lds_flat) : pack_lds(d, h->kc(), t, h->lds);
-    if (rc) return rc;
+    h->flat = next.flat;
+    h->lds = std::move(next.lds);
+    h->lds_flat = std::move(next.lds_flat);
+    h->dev_lds = next.dev;
+    h->lds_uploaded = next.uploaded;
     h->has_lds = true;
+    remember();
+    h->planned_n = n;
     return SCONV_OK;
 }
 
@@ -232,6 +243,24 @@ extern "C" int sconv_create_csr_from_arrays(const sconv_desc *desc, const int32_
         return rc;
     }
     *out = h;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_lower_offsets(const sconv_desc *desc, int32_t layout, const int32_t *rowptr, const int32_t *colidx,
+                                   int32_t *off, int32_t *step_y, int32_t *step_x)
+{
+    if (!desc || !rowptr) return SCONV_ERR_NULL;
+    int rc = validate_desc(*desc);
+    if (rc) return rc;
+    if (layout != SCONV_LAYOUT_CHW && layout != SCONV_LAYOUT_HWC) return SCONV_ERR_DESC;
+    rc = validate_csr(*desc, rowptr, colidx);
+    if (rc) return rc;
+    if (rowptr[desc->K] > 0 && !off) return SCONV_ERR_NULL;
+    lower_offsets(*desc, layout, rowptr, colidx, off);
+    const Geometry g = geometry(*desc);
+    const int per_x = layout == SCONV_LAYOUT_HWC ? desc->C : 1;
+    if (step_y) *step_y = desc->stride * g.Wp * per_x;
+    if (step_x) *step_x = desc->stride * per_x;
     return SCONV_OK;
 }
 
@@ -817,11 +846,28 @@ extern "C" void sconv_machine_gfx950(sconv_machine *m)
     m->lds_bytes_per_s = 148e12;    // aligned ds_read_b128, 242 B/clk/CU
     m->lds_bytes_per_fma = 4.0;
     m->lane_efficiency = 0.73;      // 0.9 (lanes that are outputs) x 0.8 (issue slots left after address
-                                    // arithmetic, LDS waits and barriers): the x = 1 plateau of 53-55 TFLOP/s
+                                    // arithmetic, LDS waits and barriers): CALIBRATED to the measured x = 1
+                                    // plateau of 53-55 TFLOP/s, as the paper takes alpha from its measured plateau
+    m->t_fixed = 11.4e-6;           // intercept of time against nonzeros on conv3's shape at batch 256
 }
+
+static int predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h, const sconv_machine *m,
+                   bool lowered, sconv_prediction *out);
 
 extern "C" int sconv_model_predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
                                    const sconv_machine *m, sconv_prediction *out)
+{
+    return predict(desc, N, density, h, m, false, out);
+}
+
+extern "C" int sconv_model_predict_lowered(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h,
+                                           const sconv_machine *m, sconv_prediction *out)
+{
+    return predict(desc, N, density, h, m, true, out);
+}
+
+static int predict(const sconv_desc *desc, int32_t N, double density, const sconv_csr *h, const sconv_machine *m,
+                   bool lowered, sconv_prediction *out)
 {
     if (!desc || !out) return SCONV_ERR_NULL;
     int rc = validate_desc(*desc);
@@ -846,14 +892,16 @@ extern "C" int sconv_model_predict(const sconv_desc *desc, int32_t N, double den
     }
     sconv_prediction p;
     p.flops_dense = 2.0 * desc->K * cols * g.OH * g.OW * N;
-    p.bytes_act = 4.0 * N * ((double)desc->C * desc->H * desc->W + (double)desc->K * g.OH * g.OW);
+    // direct: every input element once; lowered: the (C*R*S) x (OH*OW) matrix the lowering writes out
+    const double in_elems = lowered ? (double)desc->C * desc->R * desc->S * g.OH * g.OW : (double)desc->C * desc->H * desc->W;
+    p.bytes_act = 4.0 * N * (in_elems + (double)desc->K * g.OH * g.OW);
     p.bytes_w = 4.0 * desc->K * cols;
     p.density = x;
     p.alpha = alpha;
     p.t_dense = p.flops_dense / m->dense_flops;
     p.t_sparse_compute = alpha * x * p.flops_dense / m->dense_flops;
     p.t_sparse_bw = (p.bytes_act + m->beta * x * p.bytes_w) / m->hbm_bytes_per_s;
-    p.t_sparse = std::fmax(p.t_sparse_compute, p.t_sparse_bw);
+    p.t_sparse = std::fmax(p.t_sparse_compute, p.t_sparse_bw) + (m->t_fixed > 0 ? m->t_fixed : 0.0);
     p.speedup = p.t_dense / p.t_sparse;
     p.effective_flops = p.flops_dense / p.t_sparse;
     p.actual_flops = x * p.flops_dense / p.t_sparse;

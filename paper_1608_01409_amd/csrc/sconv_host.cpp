@@ -25,20 +25,43 @@ int validate_desc(const sconv_desc &d)
     return SCONV_OK;
 }
 
-// Figure 2's layout function on the zero-padded CHW image: f(c,r,s) = (c*Hp + r)*Wp + s.
-static void lower(const sconv_desc &d, Canonical &c)
+// Figure 2's layout function on the zero-padded image.  CHW: f(c,r,s) = (c*Hp + r)*Wp + s.  HWC (channel
+// innermost): f(c,r,s) = (r*Wp + s)*C + c.  Both are additive in the position, which is all Section 2.1 asks.
+void lower_offsets(const sconv_desc &d, int layout, const int32_t *rowptr, const int32_t *colidx, int32_t *off)
 {
     const Geometry g = geometry(d);
-    const int nnz = (int)c.colidx.size();
-    c.off.resize(nnz);
     for (int k = 0; k < d.K; ++k) {
         const int grp = k / g.Kg;
-        for (int j = c.rowptr[k]; j < c.rowptr[k + 1]; ++j) {
-            const int col = c.colidx[j];
-            const int s = col % d.S, r = (col / d.S) % d.R, ch = col / (d.S * d.R);
-            c.off[j] = ((grp * g.Cg + ch) * g.Hp + r) * g.Wp + s;
+        for (int j = rowptr[k]; j < rowptr[k + 1]; ++j) {
+            const int col = colidx[j];
+            const int s = col % d.S, r = (col / d.S) % d.R, ch = grp * g.Cg + col / (d.S * d.R);
+            off[j] = layout == SCONV_LAYOUT_HWC ? (r * g.Wp + s) * d.C + ch : (ch * g.Hp + r) * g.Wp + s;
         }
     }
+}
+
+static void lower(const sconv_desc &d, Canonical &c)
+{
+    c.off.resize(c.colidx.size());
+    lower_offsets(d, SCONV_LAYOUT_CHW, c.rowptr.data(), c.colidx.data(), c.off.data());
+}
+
+int validate_csr(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx)
+{
+    const Geometry g = geometry(d);
+    const int64_t ncol = (int64_t)g.Cg * d.R * d.S;
+    if (rowptr[0] != 0) return SCONV_ERR_CSR;
+    for (int k = 0; k < d.K; ++k)
+        if (rowptr[k + 1] < rowptr[k]) return SCONV_ERR_CSR;
+    if (rowptr[d.K] > 0 && !colidx) return SCONV_ERR_NULL;
+    for (int k = 0; k < d.K; ++k) {
+        if ((int64_t)rowptr[k + 1] - rowptr[k] > ncol) return SCONV_ERR_CSR;
+        for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
+            if (colidx[j] < 0 || colidx[j] >= ncol) return SCONV_ERR_CSR;
+            if (j > rowptr[k] && colidx[j] <= colidx[j - 1]) return SCONV_ERR_CSR;
+        }
+    }
+    return SCONV_OK;
 }
 
 int build_canonical_from_dense(const sconv_desc &d, const float *w, Canonical &out)
@@ -64,20 +87,10 @@ int build_canonical_from_dense(const sconv_desc &d, const float *w, Canonical &o
 int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx,
                                 const float *values, Canonical &out)
 {
-    const Geometry g = geometry(d);
-    const int64_t ncol = (int64_t)g.Cg * d.R * d.S;
-    if (rowptr[0] != 0) return SCONV_ERR_CSR;
-    for (int k = 0; k < d.K; ++k)
-        if (rowptr[k + 1] < rowptr[k]) return SCONV_ERR_CSR;
+    const int rc = validate_csr(d, rowptr, colidx);
+    if (rc) return rc;
     const int32_t nnz = rowptr[d.K];
-    if (nnz > 0 && (!colidx || !values)) return SCONV_ERR_NULL;
-    for (int k = 0; k < d.K; ++k) {
-        if ((int64_t)rowptr[k + 1] - rowptr[k] > ncol) return SCONV_ERR_CSR;
-        for (int32_t j = rowptr[k]; j < rowptr[k + 1]; ++j) {
-            if (colidx[j] < 0 || colidx[j] >= ncol) return SCONV_ERR_CSR;
-            if (j > rowptr[k] && colidx[j] <= colidx[j - 1]) return SCONV_ERR_CSR;
-        }
-    }
+    if (nnz > 0 && !values) return SCONV_ERR_NULL;
     out.rowptr.assign(rowptr, rowptr + d.K + 1);
     out.colidx.assign(colidx, colidx + nnz);
     out.val.assign(values, values + nnz);

@@ -97,6 +97,10 @@ struct Canonical {
 };
 
 int validate_desc(const sconv_desc &d);
+// rowptr starts at 0 and never falls, columns inside [0, Cg*R*S) and strictly ascending in each row
+int validate_csr(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx);
+// colidx -> off for a padded image stored in `layout` (a sconv_layout); the arrays are assumed valid
+void lower_offsets(const sconv_desc &d, int layout, const int32_t *rowptr, const int32_t *colidx, int32_t *off);
 int build_canonical_from_dense(const sconv_desc &d, const float *w, Canonical &out);
 int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, const int32_t *colidx,
                                 const float *values, Canonical &out);

@@ -14,6 +14,10 @@
 // memory with a bounds test standing in for the padding.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "sconv_internal.h"
 
 namespace sconv {
@@ -399,13 +403,13 @@ __global__ void __launch_bounds__(256) sconv_direct_kernel(const DirectArgs a)
 int upload(const void *host, size_t bytes, void **dev, int *hip_err)
 {
     *dev = nullptr;
-    if (bytes == 0) bytes = 16; // keep a valid pointer for empty patterns
-    hipError_t e = hipMalloc(dev, bytes);
+    const size_t room = bytes ? bytes : 16; // keep a valid pointer for empty patterns
+    hipError_t e = hipMalloc(dev, room);
     if (e != hipSuccess) {
         *hip_err = (int)e;
         return SCONV_ERR_HIP;
     }
-    if (host) {
+    if (host && bytes) {
         e = hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
             *hip_err = (int)e;
@@ -469,19 +473,34 @@ void timer_destroy(StreamTimer &t)
     t.e0 = t.e1 = nullptr;
 }
 
+// A kernel may use more than 64 KB of dynamic LDS only after it has been allowed to, once per kernel and
+// device.  The record of what has been allowed is the only state the library keeps outside its handles; it
+// is guarded, so handles may be used from different threads.
+static int allow_full_lds(const void *kern, int *hip_err)
+{
+    static std::mutex guard;
+    static std::set<std::pair<const void *, int>> allowed;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(guard);
+        if (allowed.count({kern, dev})) return SCONV_OK;
+        e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) allowed.insert({kern, dev});
+    }
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    return SCONV_OK;
+}
+
 template <int VEC, int T, int ROWS_W>
 static int launch_lds_inst(const LdsArgs &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
 {
     auto kern = sconv_lds_kernel<VEC, T, ROWS_W>;
-    static int max_set = 0; // largest dynamic LDS size this instantiation has been enabled for
-    if (lds_bytes > max_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) {
-            *hip_err = (int)e;
-            return SCONV_ERR_HIP;
-        }
-        max_set = 160 * 1024;
-    }
+    const int rc = allow_full_lds(reinterpret_cast<const void *>(kern), hip_err);
+    if (rc) return rc;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -536,15 +555,8 @@ template <int T, int R, int STEP>
 static int launch_lds2_inst(const Lds2Args &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
 {
     auto kern = sconv_lds2_kernel<T, R, STEP>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) {
-            *hip_err = (int)e;
-            return SCONV_ERR_HIP;
-        }
-        attr_set = true;
-    }
+    const int rc = allow_full_lds(reinterpret_cast<const void *>(kern), hip_err);
+    if (rc) return rc;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {

@@ -124,11 +124,19 @@ def make_uniform_weights(rng_mask, rng_val, layer: Layer, density: float) -> np.
 
 def make_skewed_weights(rng_mask, rng_val, layer: Layer, mean_density: float = 0.10,
                         max_density: float = 0.60, empty_frac: float = 0.20,
-                        pareto_a: float = 2.0) -> np.ndarray:
+                        pareto_a: float = 2.0, cluster: str = "channels") -> np.ndarray:
     """Guided-pruning-like structure: `empty_frac` of the output channels fully
     pruned, the others with a power-law density (capped at `max_density`,
-    overall mean `mean_density`), nonzeros clustered into a subset of active
-    input channels."""
+    overall mean `mean_density`).  Where a row's nonzeros go:
+
+    cluster="channels"   into a subset of active input channels (each active with
+                         probability p = min(1, 2 d)), positions inside an active
+                         channel kept independently with probability d / p;
+    cluster="positions"  same active channels, but inside each the surviving kernel
+                         positions are one contiguous run in (r, s) raster order
+                         (random start, expected length d / p of the R*S positions),
+                         so the kernel positions of a channel are clustered."""
+    assert cluster in ("channels", "positions")
     K, Cg, R, S = layer.K, layer.Cg, layer.R, layer.S
     n_empty = int(round(empty_frac * K))
     empty = np.zeros(K, dtype=bool)
@@ -152,24 +160,31 @@ def make_skewed_weights(rng_mask, rng_val, layer: Layer, mean_density: float = 0
     vals = (rng_val.standard_normal((K, Cg, R, S), dtype=np.float32) * np.float32(WEIGHT_STD)).astype(np.float32)
     vals[vals == 0] = np.float32(WEIGHT_STD)
     w = np.zeros((K, Cg, R, S), dtype=np.float32)
+    npos = R * S
     for k in range(K):
         if d[k] <= 0:
             continue
         p = min(1.0, 2.0 * d[k])
         q = d[k] / p
         active = rng_mask.random(Cg) < p
-        m = (rng_mask.random((Cg, R, S)) < q) & active[:, None, None]
+        if cluster == "channels":
+            m = (rng_mask.random((Cg, R, S)) < q) & active[:, None, None]
+        else:
+            length = np.floor(q * npos + rng_mask.random(Cg)).astype(np.int64)      # expected q * npos
+            start = np.floor(rng_mask.random(Cg) * (npos - length + 1)).astype(np.int64)
+            pos = np.arange(npos)[None, :]
+            m = ((pos >= start[:, None]) & (pos < (start + length)[:, None]) & active[:, None]).reshape(Cg, R, S)
         w[k] = np.where(m, vals[k], np.float32(0))
     return w
 
 
 def make_case(cfg_index: int, layer_index: int, layer: Layer, N: int, density: float,
-              skewed: bool = False):
+              skewed: bool = False, cluster: str = "channels"):
     """(input [N,C,H,W] fp32, weights [K,Cg,R,S] fp32 with zeros where pruned)."""
     r_in, r_mask, r_val = _streams(cfg_index, layer_index)
     x = make_input(r_in, layer, N)
     if skewed:
-        w = make_skewed_weights(r_mask, r_val, layer, mean_density=density)
+        w = make_skewed_weights(r_mask, r_val, layer, mean_density=density, cluster=cluster)
     else:
         w = make_uniform_weights(r_mask, r_val, layer, density)
     return x, w

@@ -12,11 +12,6 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
-def pytest_collection_modifyitems(config, items):
-    # GPU tests print what they are about to run, so a fault names its case.
-    pass
-
-
 @pytest.fixture(scope="session")
 def oracle():
     from oracle import sconv_oracle

@@ -258,58 +258,6 @@ def test_stream_argument_is_honoured(oracle):
     assert np.all(np.abs(out.cpu().numpy() - ref) <= TOL * ab)
 
 
-# ---------------------------------------------------------------- benchmark configurations
-def test_config0_conv3_batch1(oracle):
-    (name, N, dens), = wl.CONFIGS[0]
-    layer = wl.LAYERS[name]
-    x, w = wl.make_case(0, 0, layer, N, dens)
-    check(layer, w, x, oracle, None, what="config0")
-    check(layer, w, x, oracle, dict(kernel=1, nt=1, cb=32, waves=8, cg=1, rows_w=8, t=3), what="config0-lds")
-
-
-@pytest.mark.parametrize("li", range(4))
-def test_config1_alexnet_full_batch_sampled_images(oracle, li):
-    """Full-size launch exactly as the benchmark times it; the oracle checks whole images sampled
-    from the batch (first and last tiles, tile boundaries, a few inside)."""
-    name, N, dens = wl.CONFIGS[1][li]
-    layer = wl.LAYERS[name]
-    x, w = wl.make_case(1, li, layer, N, dens)
-    images = [0, 1, 3, 4, 7, 8, 100, 127, 128, 200, 252, 255]
-    check(layer, w, x, oracle, None, images=images, what=f"config1-{name}")
-
-
-@pytest.mark.parametrize("name", ["conv3", "conv4"])
-def test_config3_skewed_rows(oracle, name):
-    layer = wl.LAYERS[name]
-    x, w = wl.make_case(3, 0 if name == "conv3" else 1, layer, 64, 0.10, skewed=True)
-    nnz_row = (w.reshape(layer.K, -1) != 0).sum(1)
-    assert (nnz_row == 0).sum() >= 0.15 * layer.K and nnz_row.max() > 3 * nnz_row.mean()
-    check(layer, w, x, oracle, None, images=[0, 5, 31, 32, 63], what=f"skewed-{name}")
-
-
-@pytest.mark.parametrize("li", range(3))
-def test_config4_googlenet_like_and_strided(oracle, li):
-    name, N, dens = wl.CONFIGS[4][li]
-    layer = wl.LAYERS[name]
-    x, w = wl.make_case(4, li, layer, N, dens)
-    check(layer, w, x, oracle, None, images=[0, 3, 4, 33, 63], what=f"config4-{name}")
-
-
-@pytest.mark.parametrize("li", range(2))
-def test_one_by_one_layers(oracle, li):
-    name, N, dens = wl.CONFIGS[5][li]
-    layer = wl.LAYERS[name]
-    x, w = wl.make_case(5, li, layer, N, dens)
-    check(layer, w, x, oracle, None, images=[0, 3, 4, 33, 63], what=f"1x1-{name}")
-
-
-@pytest.mark.parametrize("dens", [0.01, 0.5, 1.0])
-def test_density_sweep_ends_on_conv5(oracle, dens):
-    layer = wl.LAYERS["conv5"]
-    x, w = wl.make_case(2, 3, layer, 32, dens)
-    check(layer, w, x, oracle, None, images=[0, 17, 31], what=f"sweep-{dens}")
-
-
 def check_fused(layer, w, x, oracle, plan, bias, relu, what=""):
     say(f"{what} layer={layer} N={x.shape[0]} plan={plan} bias={bias is not None} relu={relu}")
     h = B.sconv_create_csr(layer, w, plan)

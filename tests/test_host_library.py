@@ -196,19 +196,23 @@ def test_automatic_plans_for_the_benchmark_layers():
 def test_model_matches_oracle_with_paper_machine():
     layer = wl.LAYERS["conv5"]
     for (F, Bw, alpha) in [(2150e9, 122e9, 3.0), (62e9, 15e9, 1.2)]:
-        m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0)
+        m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0, 0)
         for N in (1, 144):
             for x in (0.001, 0.0197, 0.09, 0.3, 1.0):
-                got = B.sconv_model_predict(layer, N, x, machine=m)
-                ref = pm.predict(layer, N, x, F, Bw, alpha, 2.0)
-                for key, val in ref.items():
-                    g = got[key]
-                    if isinstance(val, bool):
-                        assert bool(g) == val, key
-                    elif math.isinf(val):
-                        assert math.isinf(g)
-                    else:
-                        assert math.isclose(g, val, rel_tol=1e-12), (key, g, val)
+                for lowered in (False, True):
+                    for t_fixed in (0.0, 7e-6):
+                        m.t_fixed = t_fixed
+                        got = (B.sconv_model_predict_lowered if lowered else B.sconv_model_predict)(layer, N, x, machine=m)
+                        ref = pm.predict(layer, N, x, F, Bw, alpha, 2.0, lowered=lowered, t_fixed=t_fixed)
+                        for key, val in ref.items():
+                            g = got[key]
+                            if isinstance(val, bool):
+                                assert bool(g) == val, key
+                            elif math.isinf(val):
+                                assert math.isinf(g)
+                            else:
+                                assert math.isclose(g, val, rel_tol=1e-12), (key, g, val, lowered, t_fixed)
+                m.t_fixed = 0.0
 
 
 def test_model_derived_alpha_and_realised_density():
@@ -220,7 +224,8 @@ def test_model_derived_alpha_and_realised_density():
     h = B.sconv_create_csr(layer, w)
     x = np.count_nonzero(w) / w.size
     got = B.sconv_model_predict(layer, 256, 0.5, csr=h)     # density argument replaced by the handle's
-    ref = pm.predict(layer, 256, x, m.dense_flops, m.hbm_bytes_per_s, a, m.beta)
+    ref = pm.predict(layer, 256, x, m.dense_flops, m.hbm_bytes_per_s, a, m.beta, t_fixed=m.t_fixed)
+    assert m.t_fixed > 0
     assert math.isclose(got["density"], x, rel_tol=1e-12)
     for key in ("alpha", "t_dense", "t_sparse", "speedup", "x_upper", "x_lower", "actual_flops"):
         assert math.isclose(got[key], ref[key], rel_tol=1e-12), key
@@ -231,12 +236,46 @@ def test_model_derived_alpha_and_realised_density():
     assert L.sconv_model_predict(C.byref(d), 1, 0.1, None, None, None) == B.ERR["NULL"]
 
 
+LOWER_CASES = [
+    wl.small_layer(),
+    wl.small_layer(C=4, H=7, W=6, K=4, R=2, S=3, stride=2, pad=1, groups=2),
+    wl.small_layer(C=6, H=9, W=5, K=9, R=3, S=1, stride=3, pad=2, groups=3),
+    wl.LAYERS["conv2"], wl.LAYERS["conv1"], wl.LAYERS["goog1x1"],
+]
+
+
+@pytest.mark.parametrize("layer", LOWER_CASES, ids=[f"{l.name}-{i}" for i, l in enumerate(LOWER_CASES)])
+def test_lowering_alone_for_both_layouts_is_bit_exact(oracle, layer):
+    """sconv_lower_offsets against the oracle's two lowerings, and its steps against the additivity they rest on."""
+    w = rand_w(layer, 0.2, seed=13)
+    rowptr, colidx, _ = oracle.csr_from_dense(layer, w)
+    Wp = layer.W + 2 * layer.pad
+    off, sy, sx = B.sconv_lower_offsets(layer, B.LAYOUT_CHW, rowptr, colidx)
+    assert np.array_equal(off, oracle.lower_offsets(layer, rowptr, colidx))
+    assert (sy, sx) == (layer.stride * Wp, layer.stride)
+    off_h, sy, sx = B.sconv_lower_offsets(layer, B.LAYOUT_HWC, rowptr, colidx)
+    assert np.array_equal(off_h, oracle.lower_offsets_hwc(layer, rowptr, colidx))
+    assert (sy, sx) == (layer.stride * Wp * layer.C, layer.stride * layer.C)
+    # the handle's own lowering is the CHW one
+    h = B.sconv_create_csr(layer, w)
+    assert np.array_equal(B.sconv_csr_export(h)[1], off)
+    L = B.lib()
+    d = B.make_desc(layer)
+    buf = np.zeros(len(colidx) + 1, dtype=np.int32)
+    args = (rowptr.ctypes.data_as(C.c_void_p), colidx.ctypes.data_as(C.c_void_p), buf.ctypes.data_as(C.c_void_p), None, None)
+    assert L.sconv_lower_offsets(C.byref(d), 2, *args) == B.ERR["DESC"]            # no such layout
+    assert L.sconv_lower_offsets(C.byref(d), 0, None, *args[1:]) == B.ERR["NULL"]
+    bad = colidx.copy()
+    bad[0] = layer.Cg * layer.R * layer.S
+    assert L.sconv_lower_offsets(C.byref(d), 1, args[0], bad.ctypes.data_as(C.c_void_p), *args[2:]) == B.ERR["CSR"]
+
+
 def test_gsl_decision_matches_oracle():
     cases = [(2150e9, 122e9, 3.0), (62e9, 15e9, 1.2)]
     for name in ("conv5", "conv2", "goog1x1_reduce", "goog1x1", "goog3x3"):
         layer = wl.LAYERS[name]
         for (F, Bw, alpha) in cases:
-            m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0)
+            m = B.sconv_machine(F, Bw, alpha, 2.0, 0, 0, 0, 0, 0)
             for N in (1, 64):
                 for x in (0.004, 0.015, 0.05, 0.2, 0.34, 0.9, 1.0):
                     for st in (False, True):
