@@ -77,6 +77,9 @@ def main() -> int:
             if events is not None:
                 events[i][1].record(stream)
 
+    # events first: nothing but the warm-up steps themselves runs between set-up and the timed steps
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+          for _ in range(args.steps)]
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -87,8 +90,6 @@ def main() -> int:
         torch.cuda.synchronize()
     for L in layers:  # the tiling follows the batch size at the first call
         L["plan"] = B.sconv_csr_info(L["h"])["plan"]
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-          for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -106,19 +107,29 @@ def main() -> int:
         per_layer.append(dict(layer=L["name"], kernel_us=round(ms * 1e3, 2), tflops=round(tf, 3),
                               effective_tflops=round(L["dense_flops"] / (ms * 1e-3) / 1e12, 2),
                               frac_of_fma_peak=round(tf / PEAK_FMA_TFLOPS, 4), nnz=L["nnz"], plan=L["plan"]))
+    # The target is per layer, so the headline fraction is the LOWEST of the four layers, not the one of the
+    # longest-running (and most efficient) kernel; that one is listed beside it.
+    low = min(range(len(layers)), key=lambda i: per_layer[i]["tflops"])
     dom = max(range(len(layers)), key=lambda i: per_layer[i]["kernel_us"])
-    achieved = per_layer[dom]["tflops"]
-    traffic = None
+    achieved = per_layer[low]["tflops"]
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(layers[dom]["name"], {}).get("bytes")
+            traffic = json.load(open(tpath)).get(layers[low]["name"], {}).get("bytes")
+            traffic_source = ("profiles/hbm_traffic.json: rocprofv3 FETCH_SIZE + WRITE_SIZE per launch from an earlier "
+                              "profiler run of this command, stored; not measured in this run")
         except (OSError, ValueError):
             traffic = None
+
+    def kname(i):
+        return ("sconv_lds2_kernel" if layers[i]["plan"]["kernel"] == 3 else "sconv_lds_kernel") + f" on {layers[i]['name']}"
+
     roofline = dict(bound="alu", achieved=achieved, peak=PEAK_FMA_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_FMA_TFLOPS, 4), traffic=traffic,
-                    kernel=("sconv_lds2_kernel" if layers[dom]["plan"]["kernel"] == 3 else "sconv_lds_kernel") +
-                    f" on {layers[dom]['name']}",
+                    frac=round(achieved / PEAK_FMA_TFLOPS, 4), traffic=traffic, traffic_source=traffic_source,
+                    kernel=kname(low) + " (the lowest fraction of the four layers)",
+                    longest_kernel=dict(kernel=kname(dom), achieved=per_layer[dom]["tflops"],
+                                        frac=per_layer[dom]["frac_of_fma_peak"]),
                     frac_of_published_fp32_vector=round(achieved / PEAK_FP32_PUBLISHED_TFLOPS, 4),
                     step_frac=round(value / 1e3 / PEAK_FMA_TFLOPS, 4), per_layer=per_layer)
 
