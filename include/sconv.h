@@ -152,6 +152,29 @@ int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowptr, int32_t
 int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream);
 
 /*
+ * sconv_forward for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same result bit for bit.  What sconv_forward keeps in
+ * scratch memory it allocates and grows (the partial results of tilings that
+ * split the input channels over workgroups, the phase images of strided
+ * layers) lives here in a static device array of SCONV_NOALLOC_SCRATCH_BYTES
+ * that the library's code object carries (each GPU the library runs on holds
+ * it until the process ends).  The call allocates and frees nothing, on the
+ * device or through any library, and never re-plans or uploads: the handle
+ * must already hold, on the device, the packing for this N (one earlier
+ * sconv_forward, sconv_forward_fused or sconv_tune call with the same N on this
+ * device does that; the packings of the last four tilings stay resident).
+ * SCONV_ERR_PLAN if it does not, or if the handle runs another kernel than the
+ * flat-stream one; SCONV_ERR_CAPACITY if this layer and N need more scratch
+ * than the array holds.  Nothing in the array has to start at zero (every
+ * byte that is read is written first by the same call).  Every call on a GPU
+ * shares that GPU's array: calls that overlap in time on one GPU race, also
+ * on different handles and streams.
+ */
+#define SCONV_NOALLOC_SCRATCH_BYTES (64u << 20)
+int sconv_forward_noalloc(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream);
+
+/*
  * The same with a bias and a ReLU applied before the result is stored: out =
  * max(conv + bias[k], 0).  Not part of the paper's method: the networks it
  * evaluates (Section 3) apply both after every convolution, and fusing them

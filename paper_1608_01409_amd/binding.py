@@ -51,7 +51,8 @@ EXPORTS = ["sconv_create_csr", "sconv_create_csr_from_arrays", "sconv_csr_info",
            "sconv_csr_unpack", "sconv_forward", "sconv_forward_fused", "sconv_last_hip_error", "sconv_destroy_csr", "sconv_strerror",
            "sconv_machine_gfx950", "sconv_model_predict", "sconv_gsl_decide", "sconv_csr_balance",
            "sconv_fc_forward", "sconv_fc_plan", "sconv_tune", "sconv_fc_tune", "sconv_rank_plans",
-           "sconv_lower_offsets", "sconv_model_predict_lowered"]
+           "sconv_lower_offsets", "sconv_model_predict_lowered", "sconv_forward_noalloc"]
+NOALLOC_SCRATCH_BYTES = 64 << 20
 LAYOUT_CHW, LAYOUT_HWC = 0, 1
 GSL_ACTIONS = ("exclude", "prune", "stop", "restore_dense")
 
@@ -76,6 +77,7 @@ def lib():
         L.sconv_csr_export.argtypes = [vp, vp, vp, vp, i64p]
         L.sconv_csr_unpack.argtypes = [vp, i32, vp, vp, vp, i64p]
         L.sconv_forward.argtypes = [vp, vp, vp, i32, vp]
+        L.sconv_forward_noalloc.argtypes = [vp, vp, vp, i32, vp]
         L.sconv_forward_fused.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_fc_forward.argtypes = [vp, vp, vp, i32, vp, i32, vp]
         L.sconv_fc_plan.argtypes = [vp, i32, C.POINTER(sconv_plan)]
@@ -243,6 +245,21 @@ def sconv_forward(csr: Csr, x, out=None, stream=None):
                                  C.c_void_p(s.cuda_stream))
     if rc != SCONV_OK:
         raise SconvError(rc, f"sconv_forward (hip error {lib().sconv_last_hip_error(csr.handle)})")
+    return out
+
+
+def sconv_forward_noalloc(csr: Csr, x, out, stream=None):
+    """sconv_forward without any allocation: `out` must be given, and the handle prepared by an earlier
+    sconv_forward call with the same batch size."""
+    import torch
+
+    assert out is not None
+    N, out, s = _conv_buffers(csr, x, out, stream)
+    with torch.cuda.device(x.device):
+        rc = lib().sconv_forward_noalloc(csr.handle, C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), N,
+                                         C.c_void_p(s.cuda_stream))
+    if rc != SCONV_OK:
+        raise SconvError(rc, f"sconv_forward_noalloc (hip error {lib().sconv_last_hip_error(csr.handle)})")
     return out
 
 

@@ -87,15 +87,38 @@ static int grow(void **buf, size_t *have, size_t need, int *hip_err)
     return SCONV_OK;
 }
 
+// A fixed piece of device memory handed out front to back (the entry point that must not allocate).
+struct Workspace {
+    char *base = nullptr;
+    size_t bytes = 0, used = 0;
+    void *take(size_t need)
+    {
+        const size_t at = (used + 255) & ~(size_t)255;
+        if (at + need > bytes) return nullptr;
+        used = at + need;
+        return base + at;
+    }
+};
+
 // The flat-stream kernel and, when the tiling splits the channels, the reduction of its partial results.
+// The partial results go to scratch the handle owns and grows, or into `ws` when one is given.
 static int run_flat(sconv_csr *h, const sconv_desc &kd, const LdsTiling &t, const DeviceLds &dev, const Lds2Layout &lay,
-                    const float *in, float *out, int n_kernel, int64_t rows, int64_t inner, const Epilogue &ep, void *stream)
+                    const float *in, float *out, int n_kernel, int64_t rows, int64_t inner, const Epilogue &ep, void *stream,
+                    Workspace *ws = nullptr)
 {
     if (t.p.splits <= 1) return launch_lds2(kd, t, dev, lay, in, out, n_kernel, ep, 0, stream, &h->hip_err);
     const int64_t total = rows * inner;
-    int rc = grow(&h->part_buf, &h->part_bytes, (size_t)total * t.p.splits * sizeof(float), &h->hip_err);
-    if (rc) return rc;
-    float *parts = static_cast<float *>(h->part_buf);
+    const size_t need = (size_t)total * t.p.splits * sizeof(float);
+    int rc;
+    float *parts;
+    if (ws) {
+        parts = static_cast<float *>(ws->take(need));
+        if (!parts) return SCONV_ERR_CAPACITY;
+    } else {
+        rc = grow(&h->part_buf, &h->part_bytes, need, &h->hip_err);
+        if (rc) return rc;
+        parts = static_cast<float *>(h->part_buf);
+    }
     rc = launch_lds2(kd, t, dev, lay, in, parts, n_kernel, ep, total, stream, &h->hip_err);
     if (rc) return rc;
     return launch_reduce(parts, out, t.p.splits, rows, inner, h->desc.K, ep, stream, &h->hip_err);
@@ -112,7 +135,7 @@ static bool same_plan(const sconv_plan &a, const sconv_plan &b)
 // once the new packing exists: after an error it still holds, and runs, the packing it had.
 static const size_t kPlansRemembered = 64; // batch sizes whose tiling is kept; beyond that the table starts over
 
-static int plan_lds(sconv_csr *h, int n)
+static int plan_lds(sconv_csr *h, int n, bool resident_only = false)
 {
     const sconv_desc &d = h->kdesc;
     const double avg = d.K ? (double)h->canon.val.size() / d.K : 0.0;
@@ -120,6 +143,7 @@ static int plan_lds(sconv_csr *h, int n)
     int rc;
     auto known = h->plan_of_n.find(n);
     const bool fresh = known == h->plan_of_n.end();
+    if (fresh && resident_only) return SCONV_ERR_PLAN; // never planned for this batch size
     rc = make_lds_tiling(d, fresh ? h->requested : known->second, n, avg, t); // a known tiling has every field: no search
     if (rc) return rc;
     auto remember = [&]() {
@@ -140,8 +164,11 @@ static int plan_lds(sconv_csr *h, int n)
     }
     StashedPacking next;
     if (found < h->stash.size()) {
+        if (resident_only && !h->stash[found].uploaded) return SCONV_ERR_PLAN;
         next = std::move(h->stash[found]);
         h->stash.erase(h->stash.begin() + (long)found);
+    } else if (resident_only) {
+        return SCONV_ERR_PLAN; // the packing for this tiling has been dropped: it would have to be built and uploaded
     } else {
         next.flat = t.p.kernel == 3;
         rc = next.flat ? pack_flat(d, h->kc(), t, next.lds_flat) : pack_lds(d, h->kc(), t, next.lds);
@@ -155,7 +182,9 @@ static int plan_lds(sconv_csr *h, int n)
         old.dev = h->dev_lds;
         old.uploaded = h->lds_uploaded;
         h->stash.push_back(std::move(old));
-        while (h->stash.size() > h->stash_cap) { // hipFree waits for launches that still read the arrays
+        // (resident_only: one packing left the stash and one entered it, so nothing has to go, and nothing may:
+        // hipFree is not for that caller)
+        while (!resident_only && h->stash.size() > h->stash_cap) { // hipFree waits for launches that still read the arrays
             release_arrays(h->stash.front().dev);
             h->stash.erase(h->stash.begin());
         }
@@ -385,7 +414,8 @@ extern "C" int sconv_csr_unpack(const sconv_csr *h, int32_t which, int32_t *rowp
     return export_canonical(h->desc, c, rowptr, off, values, nnz_io);
 }
 
-static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream);
+static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream,
+                        Workspace *ws = nullptr);
 
 extern "C" int sconv_forward(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream)
 {
@@ -401,7 +431,10 @@ extern "C" int sconv_forward_fused(sconv_csr *h, const float *in, float *out, in
     return forward_impl(h, in, out, N, ep, hip_stream);
 }
 
-static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream)
+// ws != nullptr: the caller forbids allocation.  Scratch then comes out of ws, and everything else the launch
+// needs (the tiling for N, its packing, the device copies) must already exist: SCONV_ERR_PLAN otherwise.
+static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, const Epilogue &ep, void *hip_stream,
+                        Workspace *ws)
 {
     if (!h || !in || !out) return SCONV_ERR_NULL;
     if (N < 1) return SCONV_ERR_BATCH;
@@ -415,23 +448,31 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     const int n_plan = N < 4 ? 4 : N;
     if (use_lds && free_choice && n_plan != h->planned_n) {
         try {
-            const int prc = plan_lds(h, n_plan);
+            const int prc = plan_lds(h, n_plan, ws != nullptr);
             if (prc) return prc;
         } catch (const std::bad_alloc &) {
             return SCONV_ERR_NOMEM;
         }
     }
+    if (ws && !(use_lds && h->flat && h->lds_uploaded)) return SCONV_ERR_PLAN;
     // the per-row-stream kernel's tiles of 4 images and more are no match for the direct kernel on 1-3 images
     if (use_lds && !h->flat && h->requested.kernel == 0 && N < 4 && h->lds.t.p.nt >= 4) use_lds = false;
     int rc;
     if (use_lds && h->phased) {
         // re-order the input into phase images (scratch owned by the handle, grown on demand)
         const size_t need = (size_t)N * h->kdesc.C * h->kdesc.H * h->kdesc.W * sizeof(float);
-        rc = grow(&h->phase_buf, &h->phase_bytes, need, &h->hip_err);
+        float *phase;
+        if (ws) {
+            phase = static_cast<float *>(ws->take(need));
+            if (!phase) return SCONV_ERR_CAPACITY;
+        } else {
+            rc = grow(&h->phase_buf, &h->phase_bytes, need, &h->hip_err);
+            if (rc) return rc;
+            phase = static_cast<float *>(h->phase_buf);
+        }
+        rc = launch_phase(h->desc, h->kdesc, in, phase, N, hip_stream, &h->hip_err);
         if (rc) return rc;
-        rc = launch_phase(h->desc, h->kdesc, in, static_cast<float *>(h->phase_buf), N, hip_stream, &h->hip_err);
-        if (rc) return rc;
-        in = static_cast<const float *>(h->phase_buf);
+        in = phase;
     }
     if (use_lds && h->flat) {
         if (!h->lds_uploaded) {
@@ -442,9 +483,15 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
             if (!rc) rc = upload(f.store_tbl.data(), f.store_tbl.size() * 4, &h->dev_lds.store_tbl, &h->hip_err);
             if (rc) return rc;
             h->lds_uploaded = true;
+            // set-up on this device: the address of the library's static scratch is looked up now, so that
+            // sconv_forward_noalloc finds it known (a failure here is that entry point's to report)
+            void *base;
+            size_t bytes;
+            int ignored = 0;
+            (void)static_scratch(&base, &bytes, &ignored);
         }
         const LdsTiling &ft = f_tiling(h);
-        return run_flat(h, h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, out_rows, out_inner, ep, hip_stream);
+        return run_flat(h, h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, out_rows, out_inner, ep, hip_stream, ws);
     }
     if (use_lds) {
         if (!h->lds_uploaded) {
@@ -465,6 +512,17 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     }
     rc = launch_direct(h->desc, h->dev_direct, in, out, N, hip_stream, &h->hip_err);
     return rc ? rc : launch_epilogue(out, out_rows, out_inner, h->desc.K, ep, hip_stream, &h->hip_err);
+}
+
+extern "C" int sconv_forward_noalloc(sconv_csr *h, const float *in, float *out, int32_t N, void *hip_stream)
+{
+    if (!h) return SCONV_ERR_NULL;
+    Workspace ws;
+    void *base = nullptr;
+    const int rc = static_scratch(&base, &ws.bytes, &h->hip_err);
+    if (rc) return rc;
+    ws.base = static_cast<char *>(base);
+    return forward_impl(h, in, out, N, Epilogue(), hip_stream, &ws);
 }
 
 // ---- fully connected layers: out_t[K][N] = W[K][C] (CSR) x in_t[C][N] -------------------------------

@@ -171,6 +171,9 @@ int launch_epilogue(float *out, int64_t rows, int64_t inner, int K, const Epilog
 int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, float *q, int N, void *stream, int *hip_err);
 int launch_direct(const sconv_desc &d, const DeviceDirect &dev, const float *in, float *out, int N,
                   void *stream, int *hip_err);
+// The library's static device scratch (SCONV_NOALLOC_SCRATCH_BYTES) on the current device: its address
+// there, looked up once per device and remembered.
+int static_scratch(void **base, size_t *bytes, int *hip_err);
 int upload(const void *host, size_t bytes, void **dev, int *hip_err);
 void release(void *dev);
 

@@ -400,6 +400,39 @@ __global__ void __launch_bounds__(256) sconv_direct_kernel(const DirectArgs a)
 
 // ------------------------------------------------------------------------------------------------
 
+// Scratch for the entry point that must not allocate: device memory the code object itself brings along,
+// one copy per GPU the library runs on, held until the process ends.  Its name is a host-side stand-in, not
+// a device address: host code only ever uses the address hipGetSymbolAddress reports for the current device.
+static __device__ __align__(256) unsigned char scratch[SCONV_NOALLOC_SCRATCH_BYTES];
+
+int static_scratch(void **base, size_t *bytes, int *hip_err)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *ptr[kMaxDevices] = {};
+    *base = nullptr;
+    *bytes = 0;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(guard);
+        if (!ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
+            if (e == hipSuccess) ptr[dev] = p;
+        }
+        if (e == hipSuccess) *base = ptr[dev];
+    }
+    if (e != hipSuccess) {
+        *hip_err = (int)e;
+        return SCONV_ERR_HIP;
+    }
+    *bytes = SCONV_NOALLOC_SCRATCH_BYTES;
+    return SCONV_OK;
+}
+
 int upload(const void *host, size_t bytes, void **dev, int *hip_err)
 {
     *dev = nullptr;
