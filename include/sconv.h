@@ -54,18 +54,23 @@ typedef struct {
 /*
  * How the kernels tile a layer.  Zero in every field asks the library to choose.
  * kernel: 1 = LDS-tiled kernel with one nonzero stream per row (stride 1),
- * 3 = LDS-tiled kernel with one stream per wave (stride 1, nt = 4),
+ * 3 = LDS-tiled kernel with one stream per wave (stride 1, nt = 4), two block
+ * buffers in LDS and a barrier per channel block,
+ * 4 = the same kernel with three block buffers and no barriers: the waves of a
+ * workgroup tell each other through counters in LDS which blocks have landed
+ * and drift up to half a block apart instead of all waiting for the slowest at
+ * every block (takes everything kernel 3 takes: strips, splits, bands),
  * 2 = direct kernel (any stride).
  * For the LDS-tiled kernels one workgroup owns `nt` images (1, or a multiple of
  * 4), a band of `band` consecutive output rows (0 = choose; OH = the whole
  * image) and `waves/cg * rows_w` CSR rows; it walks the input channels in
  * blocks of `cb`; each wave keeps rows_w x t x (4 if nt >= 4 else 1)
- * accumulators per lane.  `strip` (kernel 3 only): 0 = the lanes of a wave
+ * accumulators per lane.  `strip` (kernels 3 and 4 only): 0 = the lanes of a wave
  * span 64 consecutive cells of the padded plane, chunk after chunk; w > 0 =
  * they span a block of 64/w output rows by w output columns and the t chunks of
  * a wave are t such blocks side by side (t*w >= OW, band <= cg * (64/w)),
- * which wastes fewer lanes when OW is a little under t*w.  `splits` (kernel 3
- * only; 0 or 1 = none): that many workgroups share the channel blocks of a
+ * which wastes fewer lanes when OW is a little under t*w.  `splits` (kernels 3
+ * and 4 only; 0 or 1 = none): that many workgroups share the channel blocks of a
  * tile, for launches that would otherwise leave compute units idle; each
  * stores its partial results into scratch memory the handle owns and a second
  * launch adds them up in a fixed order.

@@ -22,6 +22,20 @@ data, not code, so the rows of a wave share one stream with no per-row padding.
            multiplied.  Lanes whose cell is zero padding carry an out-of-range buffer offset and
            receive 0 from the hardware's range check; lanes past the end of a plane are masked off.
   stores   row bases from row_of, per-lane store offsets from a table (-1 = not an output).
+
+Two ways of keeping the waves of a workgroup in step with the block buffers (template parameter FLOW):
+
+  barrier  two buffers, one s_barrier per channel block: past it every wave's loads of block b have landed
+           and every wave is done with the buffer that block b+1 is about to overwrite.  Every block then
+           costs what its slowest wave costs, plus a collective start-up (all waves issue their staging
+           loads and first reads at once) and a tail in which ever fewer waves are left working.
+  flow     three buffers and no barrier after the first.  Each wave issues its share of block b+1's loads
+           when it starts block b (into the buffer block b-2 used), and a few chunks into block b, once
+           those loads have landed, adds 1 to an LDS counter S[b+1].  A wave starts block b when S[b]
+           shows every wave's share of block b present.  A wave that signals S[b+1] is inside block b, so
+           S[b+1] complete also means every wave has left block b-1: its buffer may be overwritten with
+           block b+2.  Waves drift up to about half a block apart; nobody waits for the slowest wave at
+           every block.
 """
 from __future__ import annotations
 
@@ -53,17 +67,19 @@ SOFF, SS, SNCH, STGT = 96, 97, 98, 99            # stream byte offset; staging t
 SNXT = 31                                        # chunks in the next block's segment
 SX0, SX1 = SSEG, SSEG + 1                        # store address pair: the segment pointer is done by then
 MAX_VGPR = 128
+SIGNAL_AFTER = 2             # flow: a wave reports its staged block at the second first-of-three chunk (chunk 3) or at the segment's end
 
 # kernel-argument offsets the asm reads (checked by static_asserts next to the struct)
 OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
 
 OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase", "slab0", "slabstep", "nslab",
-       "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff", "outp_hi", "nch", "nblk", "bias", "flags"]
+       "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff", "outp_hi", "nch", "nblk", "bias", "flags", "nwv"]
+IO_OPS = ["ctr"]               # in/out: LDS byte address of the counter of the block the wave is in (flow only)
 FLAG_RELU = 0                  # bit of the flags operand
-OP = {n: f"%[{n}]" for n in OPS}
+OP = {n: f"%[{n}]" for n in OPS + IO_OPS}
 
 
-def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
+def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False) -> str:
     assert CH % D == 0 and R * T * 4 <= 256
     nacc = R * T * 4
     ring_regs = D * T * 4
@@ -75,7 +91,8 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     RING0 = ACC0 + nacc
     VA0 = RING0 + ring_regs
     VLB = VA0 + n_va        # lane base for the current buffer
-    assert VLB + 1 <= MAX_VGPR
+    VS0, VS1 = VLB + 1, VLB + 2     # scratch of the counter operations (flow)
+    assert VS1 + 1 <= MAX_VGPR
 
     def q(slot, t, e=None):
         b = RING0 + (slot * T + t) * 4
@@ -94,6 +111,32 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     def label(stem):
         uid[0] += 1
         return f".L{stem}{uid[0]}_%="
+
+    def signal(off):
+        """This wave's share of a block has landed: add 1 to the block's counter at ctr + off (one lane)."""
+        emit("s_waitcnt vmcnt(0)")
+        emit(f"s_add_u32 s{STMP}, {OP['ctr']}, {off}")
+        emit(f"v_mov_b32 v{VS0}, s{STMP}")
+        emit(f"v_mov_b32 v{VS1}, 1")
+        emit("s_mov_b64 exec, 1")
+        emit(f"ds_add_u32 v{VS0}, v{VS1}")
+        emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
+
+    def poll():
+        """Wait until every wave has added its 1 to the counter at ctr.  Every wave of the workgroup reaches
+        its signal for this counter without waiting for anything later than the previous counter, so the
+        loop ends."""
+        again, go = label("poll"), label("go")
+        emit(f"v_mov_b32 v{VS0}, {OP['ctr']}")
+        emit(f"{again}:")
+        emit(f"ds_read_b32 v{VS1}, v{VS0}")
+        emit("s_waitcnt lgkmcnt(0)")
+        emit(f"v_readfirstlane_b32 s{STMP}, v{VS1}")
+        emit(f"s_cmp_ge_u32 s{STMP}, {OP['nwv']}")
+        emit(f"s_cbranch_scc1 {go}")
+        emit("s_sleep 1")
+        emit(f"s_branch {again}")
+        emit(f"{go}:")
 
     def stage(tgt):
         """Issue the DMA loads of the next block (channels SSOFF.. , min(SCB, SREM) of them) into LDS at tgt."""
@@ -133,9 +176,19 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
         emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{STMP}")
         emit(f"s_sub_u32 s{SREM}, s{SREM}, s{SNCH}")
 
-    def body(A, B, N, n=CH):
+    def body(A, B, N, n=CH, check=False):
         """One chunk: multiply the first n entries of A (8, or 4 for the half chunk that may open a segment);
-        reads of the entries D ahead (A's tail, B's head) are issued."""
+        reads of the entries D ahead (A's tail, B's head) are issued.  check (flow): this body counts down
+        vcc_lo, the chunks to go before the landing of the staged block is reported."""
+        if check:
+            nosig = label("nosig")
+            emit("s_cmp_eq_u32 vcc_lo, 0")
+            emit(f"s_cbranch_scc1 {nosig}")
+            emit("s_sub_u32 vcc_lo, vcc_lo, 1")
+            emit("s_cmp_lg_u32 vcc_lo, 0")
+            emit(f"s_cbranch_scc1 {nosig}")
+            signal(4)
+            emit(f"{nosig}:")
         def entry_w1(p):
             return w1(A, p) if p < n else w1(B, p - n)
         def fetch_next():
@@ -203,12 +256,19 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
     emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
     emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
+    if flow:
+        signal(0)                                          # my share of the first block is in LDS
+        emit("s_mov_b32 vcc_lo, 0")                        # no landing left to report
 
     # ------------------------------------------------------------------ channel blocks
     blk, nostage, segdone, noreads = label("blk"), label("nostage"), label("segdone"), label("noreads")
     emit(f"{blk}:")
-    emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
-    emit("s_barrier")
+    if flow:
+        emit("s_waitcnt lgkmcnt(0)")
+        poll()                                             # every wave's share of this block is in LDS
+    else:
+        emit("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        emit("s_barrier")
     emit(f"s_lshr_b32 s{SHALF}, s{SNXT}, 31")              # bit 31: the segment opens with a half chunk
     emit(f"s_lshl_b32 s{SCNT}, s{SNXT}, 6")                # this block's chunks -> where its loads end
     emit(f"s_add_u32 s{SCNT}, s{SCNT}, s{SOFF}")
@@ -227,9 +287,19 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"{noreads}:")
     emit(f"s_cmp_le_u32 s{SLEFT}, 1")                      # the last block stages nothing
     emit(f"s_cbranch_scc1 {nostage}")
-    emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
-    emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
-    stage(STGT)
+    if flow:
+        # the buffer after the current one, round the three: block b-2's, which every wave has left
+        emit(f"s_mul_i32 s{STMP}, s{SSTRIDE}, 3")
+        emit(f"s_add_u32 s{STGT}, s{SBUF}, s{SSTRIDE}")
+        emit(f"s_cmp_eq_u32 s{STGT}, s{STMP}")
+        emit(f"s_cselect_b32 s{STGT}, 0, s{STGT}")
+        emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
+        stage(STGT)
+        emit(f"s_mov_b32 vcc_lo, {SIGNAL_AFTER}")          # report the landing that many first-of-three chunks on
+    else:
+        emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
+        emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
+        stage(STGT)
     emit(f"{nostage}:")
     emit(f"s_cmp_eq_u32 s{SCNT}, s{SOFF}")
     emit(f"s_cbranch_scc1 {segdone}")
@@ -240,7 +310,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_cmp_lg_u32 s{SHALF}, 0")
     emit(f"s_cbranch_scc1 {half}")
     emit(f"{loop}:")
-    body(SA, SB, SN)
+    body(SA, SB, SN, check=flow)
     emit(f"s_cbranch_scc0 {exit1}")
     emit(f"{second}:")
     body(SB, SN, SA)
@@ -268,7 +338,20 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     emit(f"s_branch {second}")
     emit(f"{segdone}:")
     emit("s_waitcnt lgkmcnt(0)")                # the last request lands before its registers are reused
-    emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
+    if flow:
+        reported = label("reported")
+        emit("s_cmp_eq_u32 vcc_lo, 0")          # a short segment ends before the landing was reported
+        emit(f"s_cbranch_scc1 {reported}")
+        signal(4)
+        emit("s_mov_b32 vcc_lo, 0")
+        emit(f"{reported}:")
+        emit(f"s_add_u32 {OP['ctr']}, {OP['ctr']}, 4")
+        emit(f"s_mul_i32 s{STMP}, s{SSTRIDE}, 3")
+        emit(f"s_add_u32 s{SBUF}, s{SBUF}, s{SSTRIDE}")
+        emit(f"s_cmp_eq_u32 s{SBUF}, s{STMP}")
+        emit(f"s_cselect_b32 s{SBUF}, 0, s{SBUF}")
+    else:
+        emit(f"s_sub_u32 s{SBUF}, s{SSTRIDE}, s{SBUF}")
     emit(f"s_sub_u32 s{SLEFT}, s{SLEFT}, 1")
     emit(f"s_cmp_lg_u32 s{SLEFT}, 0")
     emit(f"s_cbranch_scc1 {blk}")
@@ -359,6 +442,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     vregs = {"lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff"}
     cnames = {"outp": "outp_lo"}
     ins = ", ".join(f'[{n}] "{"v" if n in vregs else "s"}"({cnames.get(n, n)})' for n in OPS)
+    outs = ", ".join(f'[{n}] "+s"({n})' for n in IO_OPS)
     text = []
     for ins_ in L:
         text.append(f'            "{ins_}\\n\\t"')
@@ -367,18 +451,18 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int) -> str:
     clob += ['"vcc"', '"scc"', '"memory"']
     return f"""
 template <>
-struct Lds2Asm<{T}, {R}, {step}> {{
+struct Lds2Asm<{T}, {R}, {step}, {"true" if flow else "false"}> {{
     static constexpr int kDepth = {D};
     static __device__ __forceinline__ void run(unsigned long long kern, int4v rsrc, const unsigned *segp, const int *rowp,
                                                unsigned outp_lo, unsigned outp_hi, unsigned soff0, unsigned nimg,
                                                unsigned lim, unsigned ldsbase, unsigned slab0, unsigned slabstep,
                                                unsigned nslab, unsigned lane_byte, unsigned voff0, unsigned voff1,
                                                unsigned voff2, unsigned voff3, unsigned tbloff, unsigned nch, unsigned nblk,
-                                               unsigned long long bias, unsigned flags)
+                                               unsigned long long bias, unsigned flags, unsigned nwv, unsigned ctr)
     {{
         asm volatile(
 {chr(10).join(text)}
-            :
+            : {outs}
             : {ins}
             : {", ".join(clob)});
     }}
@@ -388,9 +472,10 @@ struct Lds2Asm<{T}, {R}, {step}> {{
 
 def generate() -> str:
     parts = ["// GENERATED by gen_lds2.py -- do not edit; edit the generator and rebuild.\n",
-             "template <int T, int R, int STEP>\nstruct Lds2Asm;\n"]
+             "template <int T, int R, int STEP, bool FLOW>\nstruct Lds2Asm;\n"]
     for s in SHAPES:
         parts.append(gen_shape(*s))
+        parts.append(gen_shape(*s, flow=True))
     parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r}, {st})" for t, r, _, _, st in SHAPES) + "\n")
     parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
                  f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")

@@ -170,7 +170,7 @@ static int plan_lds(sconv_csr *h, int n, bool resident_only = false)
     } else if (resident_only) {
         return SCONV_ERR_PLAN; // the packing for this tiling has been dropped: it would have to be built and uploaded
     } else {
-        next.flat = t.p.kernel == 3;
+        next.flat = is_flat_kernel(t.p.kernel);
         rc = next.flat ? pack_flat(d, h->kc(), t, next.lds_flat) : pack_lds(d, h->kc(), t, next.lds);
         if (rc) return rc;
     }
@@ -204,7 +204,7 @@ static int finish_create(sconv_csr *h, const sconv_plan *plan)
 {
     std::memset(&h->requested, 0, sizeof(h->requested));
     if (plan) h->requested = *plan;
-    if (h->requested.kernel < 0 || h->requested.kernel > 3) return SCONV_ERR_PLAN;
+    if (h->requested.kernel < 0 || h->requested.kernel > 4) return SCONV_ERR_PLAN;
     const sconv_desc &d = h->desc;
     int rc = pack_direct(d, h->canon, h->direct);
     if (rc) return rc;
@@ -222,7 +222,7 @@ static int finish_create(sconv_csr *h, const sconv_plan *plan)
         // tuned for a large batch until the first forward call says otherwise; small ones go to the direct kernel
         rc = plan_lds(h, h->requested.nt ? h->requested.nt : 256);
         if (rc != SCONV_OK && h->requested.kernel != 0) return rc;
-    } else if (h->requested.kernel == 1 || h->requested.kernel == 3) {
+    } else if (h->requested.kernel == 1 || is_flat_kernel(h->requested.kernel)) {
         return SCONV_ERR_PLAN;
     }
     return SCONV_OK;
@@ -578,7 +578,7 @@ static int fc_mapping(const sconv_csr *h, int N, sconv_desc &kd, int &tiles)
 static sconv_plan fc_request(const sconv_csr *h)
 {
     sconv_plan req = h->requested;
-    req.kernel = 3;
+    req.kernel = req.kernel == 4 ? 4 : 3;
     req.nt = 4;
     req.band = 0;
     req.strip = 0;

@@ -126,18 +126,19 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     if (p.band < 0 || p.band > g.OH) return SCONV_ERR_PLAN;
     if (p.waves % p.cg) return SCONV_ERR_PLAN;
     t.p = p;
-    if (p.kernel != 3) t.p.kernel = 1;
+    if (!is_flat_kernel(p.kernel)) t.p.kernel = 1;
+    const bool flat = is_flat_kernel(t.p.kernel), flow = t.p.kernel == 4;
     t.vec = (p.nt % 4 == 0) ? 4 : 1;
     if ((64 * t.vec) % p.nt) return SCONV_ERR_PLAN;
-    if (p.strip < 0 || p.strip > 64 || (p.strip && t.p.kernel != 3)) return SCONV_ERR_PLAN;
-    if (t.p.kernel == 3) {
+    if (p.strip < 0 || p.strip > 64 || (p.strip && !flat)) return SCONV_ERR_PLAN;
+    if (flat) {
         if (p.nt != 4 || !lds2_kernel_available(p.t, p.rows_w, p.strip ? p.strip : 64)) return SCONV_ERR_PLAN;
     } else if (!lds_kernel_available(t.vec, p.t, p.rows_w)) {
         return SCONV_ERR_PLAN;
     }
     t.strip_rows = p.strip ? 64 / p.strip : 0;
     t.out_pos = 1;
-    if (p.splits < 0 || (p.splits > 1 && t.p.kernel != 3)) return SCONV_ERR_PLAN;
+    if (p.splits < 0 || (p.splits > 1 && !flat)) return SCONV_ERR_PLAN;
     if (t.p.splits == 0) t.p.splits = 1;
     if (t.p.band == 0) t.p.band = p.strip ? std::min(g.OH, p.cg * t.strip_rows) : g.OH;
     t.n_bands = ceil_div(g.OH, t.p.band);
@@ -178,10 +179,13 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     const int64_t page = (int64_t)t.page_cells * p.nt;
     if (page < (int64_t)d.pad * p.nt) return SCONV_ERR_PLAN;
     const int64_t stride = (block + page + 3) / 4 * 4;
-    t.n_bufs = t.nblk > 1 ? 2 : 1;
-    if (stride * t.n_bufs * 4 > 160 * 1024) return SCONV_ERR_PLAN;
+    // barrier variant: two buffers; flow variant: three, and one counter per block behind them
+    t.n_bufs = std::min(flow ? 3 : 2, t.nblk);
+    const int64_t ctr_bytes = flow ? ((int64_t)t.nblk * 4 + 15) / 16 * 16 : 0;
+    if (stride * t.n_bufs * 4 + ctr_bytes > 160 * 1024) return SCONV_ERR_PLAN;
     t.buf_stride_floats = (int)stride;
-    t.lds_bytes = (int)(stride * t.n_bufs * 4);
+    t.ctr_bytes_at = flow ? (int)(stride * t.n_bufs * 4) : 0;
+    t.lds_bytes = (int)(stride * t.n_bufs * 4 + ctr_bytes);
     t.zero_page = (unsigned)(block * 4);
     return SCONV_OK;
 }
@@ -282,6 +286,8 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
 
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
                               std::vector<std::pair<double, LdsTiling>> *all);
+// whether the library, left to itself, considers the flow variant of the flat-stream kernel
+static const bool kFlowByDefault = false;
 
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
 {
@@ -325,8 +331,8 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
         if (!rc && all) all->emplace_back(0.0, out);
         return rc;
     }
-    if (req.strip && req.kernel && req.kernel != 3) return SCONV_ERR_PLAN;
-    const int kinds[2] = {3, 1};
+    if (req.strip && req.kernel && !is_flat_kernel(req.kernel)) return SCONV_ERR_PLAN;
+    const int kinds[3] = {4, 3, 1};
 
     double best = -1;
     const int nts_big[] = {4, 8, 16}; // 8 and 16 only on request
@@ -339,16 +345,18 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
         for (int waves : {4, 8, 16}) {
             if (req.waves && req.waves != waves) continue;
             if (waves % cg) continue;
-            for (int ki = 0; ki < 2; ++ki)
+            for (int ki = 0; ki < 3; ++ki)
             for (int rows_w = 1; rows_w <= 24; ++rows_w) {
                 const int kind = kinds[ki];
+                const bool flat = is_flat_kernel(kind);
                 if (req.kernel && req.kernel != kind) continue;
-                if (strip && kind != 3) continue;
+                if (strip && !flat) continue;
                 // left to itself the library uses flat streams for tiles of 4 images and per-row
                 // streams only for the small-batch tiles the flat kernel does not cover
-                if (!req.kernel && (kind == 3) != (nt == 4)) continue;
-                if (kind == 3 ? (nt != 4 || !lds2_kernel_available(T, rows_w, strip ? strip : 64))
-                              : !lds_kernel_available(vec, T, rows_w))
+                if (!req.kernel && flat != (nt == 4)) continue;
+                if (!req.kernel && kind == 4 && !kFlowByDefault) continue;
+                if (flat ? (nt != 4 || !lds2_kernel_available(T, rows_w, strip ? strip : 64))
+                         : !lds_kernel_available(vec, T, rows_w))
                     continue;
                 if (req.rows_w && req.rows_w != rows_w) continue;
                 for (int wpc_target : {1, 2, 4}) {
@@ -357,8 +365,12 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                     const int64_t per_ch = (int64_t)(band + d.R - 1) * Wl * nt * 4;
                     const int64_t page_cells = strip ? (band - 1) * Wl + T * strip : cg * T * 64 * vec / nt;
                     const int64_t fixed = page_cells * nt * 4 + 16;
-                    int cb = g.Cg; // one block, one buffer, if it fits; else two buffers
-                    if (fixed + per_ch * cb > budget) cb = (int)((budget / 2 - fixed) / per_ch);
+                    int cb = g.Cg; // one block, one buffer, if it fits; else two buffers (flow: three)
+                    if (fixed + per_ch * cb > budget) {
+                        cb = (int)((budget / 2 - fixed) / per_ch);
+                        // flow: two buffers only if the layer then has two blocks, else a third of the budget each
+                        if (kind == 4 && (cb < 1 || ceil_div(g.Cg, cb) > 2)) cb = (int)(((budget - 64) / 3 - fixed) / per_ch);
+                    }
                     if (req.cb) cb = req.cb;
                     if (cb < 1) continue;
                     // even out the blocks
@@ -366,13 +378,13 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                     // channel blocks of a tile shared by several workgroups, when there are too few tiles
                     static const int split_choices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
                     for (int sp : split_choices) {
-                        if (req.splits ? sp != 1 : (sp > 1 && kind != 3)) continue;
+                        if (req.splits ? sp != 1 : (sp > 1 && !flat)) continue;
                         const int splits = req.splits ? req.splits : sp;
                         sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip, splits};
                         LdsTiling t;
                         if (fill_tiling(d, p, t) != SCONV_OK) continue;
                         if (!req.splits && t.p.splits != sp) continue; // the same as a smaller choice
-                        const double c = kind == 3 ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
+                        const double c = flat ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
                                                    : tiling_cost(d, t, N_hint, avg_row_nnz);
                         if (all) all->emplace_back(c, t);
                         if (best < 0 || c < best) {

@@ -56,7 +56,8 @@ struct LdsTiling {
     int nkt;            // K tiles per group
     int wave_slots;     // groups * nkt * rg
     int n_slabs;        // 64-float slabs per channel plane (staging granule)
-    int n_bufs;         // LDS block buffers: 2 (double-buffered) unless the layer is a single block
+    int n_bufs;         // LDS block buffers: 2 (double-buffered; 3 for the flow variant) unless the layer has fewer blocks
+    int ctr_bytes_at;   // flow variant: byte offset in LDS of its per-block counters (nblk dwords), else 0
     int buf_stride_floats; // floats from one buffer to the next: block + zero page, multiple of 4
     int lds_bytes;      // dynamic LDS per workgroup
     unsigned zero_page; // byte offset, relative to a buffer, of its all-zero page (padding entries)
@@ -71,6 +72,10 @@ struct PackedLds {
     std::vector<int32_t> seg_ptr;  // [wave_slot][nblk][rows_w + 1] -> index into pairs
     std::vector<int32_t> row_of;   // [wave_slot][rows_w] -> output channel or -1
 };
+
+// plan.kernel values that run the flat-stream kernel: 3 = a barrier per channel block, two block buffers;
+// 4 = the flow variant, three buffers and per-block counters instead of barriers.  Same packing for both.
+inline bool is_flat_kernel(int kernel) { return kernel == 3 || kernel == 4; }
 
 // Packing for the flat-stream kernel (tiles of 4 images).  One stream per (wave slot, channel block)
 // holding the nonzeros of all rows of the slot in that block, padded to whole chunks of 8 entries:

@@ -235,6 +235,7 @@ struct Lds2Args {
     long long split_stride;  // floats from one part's partial results to the next (out then is the workspace)
     const float *bias;       // [K] added to every output of row k, or null
     int relu;                // outputs below zero become zero
+    int ctr_bytes_at;        // flow: LDS byte offset of the per-block landing counters (one dword per block)
 };
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -249,7 +250,7 @@ static_assert(offsetof(Lds2Args, img_stride_bytes) == SCONV_LDS2_OFF_CONSTS + 28
 constexpr unsigned kSkipLane = 0xFFFFFFFFu; // lane past the end of a plane: writes nothing
 constexpr unsigned kZeroLane = 0x80000000u; // padding cell: beyond num_records, the load returns 0
 
-template <int T, int R, int STEP>
+template <int T, int R, int STEP, bool FLOW>
 __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
 {
     extern __shared__ float4 smem4[];
@@ -321,6 +322,13 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
             const int b = pl / a.cb, cl = pl - b * a.cb;
             z[((b * a.buf_stride_bytes + cl * a.plane_bytes) >> 4) + cell] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        if (FLOW) {
+            // the landing counters of this workgroup's blocks start at zero; this is the only barrier of the
+            // kernel: behind it the zero pages and the counters are in place for every wave
+            unsigned *ctr = reinterpret_cast<unsigned *>(reinterpret_cast<char *>(smem4) + a.ctr_bytes_at);
+            for (int i = tid; i < nblk_here; i += blockDim.x) ctr[i] = 0u;
+            __syncthreads();
+        }
     }
 
     const float *in_tile = a.in + (size_t)tile * a.in_tile;
@@ -348,7 +356,7 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     }
     const unsigned long long bias = (unsigned long long)a.bias;
     const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane(a.relu ? 1 : 0);
-    Lds2Asm<T, R, STEP>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
+    Lds2Asm<T, R, STEP, FLOW>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
                        a.seg + ((size_t)wslot * a.nblk + blk0) * 2,
                        a.row_of + (size_t)wslot * R,
                        __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
@@ -357,7 +365,8 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
                        (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)(cell0 * 16), voff[0],
                        voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4),
                        (unsigned)__builtin_amdgcn_readfirstlane(nch_here), (unsigned)__builtin_amdgcn_readfirstlane(nblk_here),
-                       bias, flags);
+                       bias, flags, (unsigned)__builtin_amdgcn_readfirstlane(n_waves),
+                       (unsigned)__builtin_amdgcn_readfirstlane(ldsbase + (unsigned)a.ctr_bytes_at));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -584,10 +593,10 @@ int launch_lds(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, co
     return SCONV_ERR_PLAN;
 }
 
-template <int T, int R, int STEP>
+template <int T, int R, int STEP, bool FLOW>
 static int launch_lds2_inst(const Lds2Args &a, int grid, int threads, int lds_bytes, hipStream_t s, int *hip_err)
 {
-    auto kern = sconv_lds2_kernel<T, R, STEP>;
+    auto kern = sconv_lds2_kernel<T, R, STEP, FLOW>;
     const int rc = allow_full_lds(reinterpret_cast<const void *>(kern), hip_err);
     if (rc) return rc;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, s, a);
@@ -609,7 +618,7 @@ bool lds2_kernel_available(int t, int rows_w, int step)
 
 int lds2_depth(int t, int rows_w)
 {
-#define X(TT, RW, ST) if (t == TT && rows_w == RW && ST == 64) return Lds2Asm<TT, RW, ST>::kDepth;
+#define X(TT, RW, ST) if (t == TT && rows_w == RW && ST == 64) return Lds2Asm<TT, RW, ST, false>::kDepth;
     SCONV_LDS2_SHAPES(X)
 #undef X
     return 0;
@@ -735,6 +744,7 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     a.page_bytes = t.page_cells * 16;
     a.strip = t.p.strip; a.strip_rows = t.strip_rows;
     a.n_bufs = t.n_bufs;
+    a.ctr_bytes_at = t.ctr_bytes_at;
     // with several parts the kernel stores partial sums into the workspace `out` points to, part after part,
     // and the reduction that follows applies the epilogue
     a.split_stride = a.splits > 1 ? split_stride : 0;
@@ -757,6 +767,7 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     if ((t.n_slabs + t.p.waves - 1) / t.p.waves > 4) return SCONV_ERR_PLAN;
     if (t.lds_bytes % 16 || t.lds_bytes > 160 * 1024 || a.block_bytes % 16 || a.buf_stride_bytes % 16) return SCONV_ERR_PLAN;
     if (a.block_bytes + a.page_bytes > a.buf_stride_bytes) return SCONV_ERR_PLAN;
+    if ((int64_t)a.buf_stride_bytes * t.n_bufs > t.lds_bytes) return SCONV_ERR_PLAN;
     if (t.p.rows_w * t.p.t * 4 > 256) return SCONV_ERR_PLAN;
     a.img_stride_bytes = (int)(lay.out_img * 4);
     const int64_t grid64 = (int64_t)a.n_tiles * a.units;
@@ -765,8 +776,13 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int step = t.p.strip ? t.p.strip : 64;
     if (t.p.strip && (t.strip_rows < 1 || t.strip_rows * t.p.strip > 64 || t.p.band > t.p.cg * t.strip_rows)) return SCONV_ERR_PLAN;
+    const bool flow = t.p.kernel == 4;
+    if (flow != (t.ctr_bytes_at > 0) || (flow && t.ctr_bytes_at + 4 * t.nblk > t.lds_bytes)) return SCONV_ERR_PLAN;
+    if (t.n_bufs != (flow ? std::min(3, t.nblk) : std::min(2, t.nblk))) return SCONV_ERR_PLAN;
 #define X(TT, RW, ST) \
-    if (t.p.t == TT && t.p.rows_w == RW && step == ST) return launch_lds2_inst<TT, RW, ST>(a, grid, threads, t.lds_bytes, s, hip_err);
+    if (t.p.t == TT && t.p.rows_w == RW && step == ST) \
+        return flow ? launch_lds2_inst<TT, RW, ST, true>(a, grid, threads, t.lds_bytes, s, hip_err) \
+                    : launch_lds2_inst<TT, RW, ST, false>(a, grid, threads, t.lds_bytes, s, hip_err);
     SCONV_LDS2_SHAPES(X)
 #undef X
     return SCONV_ERR_PLAN;

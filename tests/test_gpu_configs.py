@@ -64,6 +64,16 @@ def test_config2_alexnet_batch256_every_image(oracle, li):
     full_check(layer, w, x, oracle, f"config2-{name}")
 
 
+@pytest.mark.parametrize("li", range(4))
+def test_config2_alexnet_batch256_every_image_flow_variant(oracle, li):
+    """The same four launches through the flow variant of the kernel (three buffers, counters instead of barriers)."""
+    name, N, dens = wl.CONFIGS[1][li]
+    layer = wl.LAYERS[name]
+    x, w = wl.make_case(1, li, layer, N, dens)
+    info = full_check(layer, w, x, oracle, f"config2-flow-{name}", dict(kernel=4))
+    assert info["plan"]["kernel"] == 4
+
+
 @pytest.mark.parametrize("dens", wl.SWEEP_DENSITIES)
 @pytest.mark.parametrize("li", range(4))
 def test_config3_density_sweep_batch256_every_image(oracle, li, dens):

@@ -77,6 +77,14 @@ PLANS = [
 ]
 
 
+def flow(plan):
+    """The same tiling on the flow variant of the flat-stream kernel (three buffers, counters instead of barriers)."""
+    return dict(plan, kernel=4)
+
+
+PLANS += [flow(p) for p in PLANS if p and p.get("kernel") == 3]
+
+
 @pytest.mark.parametrize("plan", PLANS, ids=[str(i) for i in range(len(PLANS))])
 def test_every_kernel_shape_on_a_ragged_batch(oracle, plan):
     # 21 images: several tiles of 4/8/16 and a ragged last one; 25 rows per group: ragged row tiles
@@ -117,8 +125,12 @@ FLAT_SHAPES = [
 ]
 
 
+FLAT_SHAPES += [(layer, flow(p)) for layer, p in FLAT_SHAPES]
+
+
 def _shape_id(p):
-    return f"T{p['t']}R{p['rows_w']}cg{p['cg']}" + (f"strip{p['strip']}b{p['band']}" if p.get("strip") else "")
+    return (f"k{p['kernel']}T{p['t']}R{p['rows_w']}cg{p['cg']}cb{p['cb']}w{p['waves']}" +
+            (f"strip{p['strip']}b{p['band']}" if p.get("strip") else ""))
 
 
 @pytest.mark.parametrize("case", FLAT_SHAPES, ids=[_shape_id(p) for _, p in FLAT_SHAPES])
@@ -165,7 +177,8 @@ def _random_layer(rng):
 @pytest.mark.parametrize("seed", range(40))
 def test_random_layers_automatic_plan(oracle, seed):
     """Seeded random geometry (kernel sizes 1-5, strides 1-3, pads 0-3, groups 1-3, images up to 30x30),
-    random density and batch: whatever the library chooses must match the oracle."""
+    random density and batch: whatever the library chooses must match the oracle, and so must its choice
+    among the tilings of the flow variant."""
     rng = np.random.default_rng(7000 + seed)
     layer = _random_layer(rng)
     N = int(rng.choice([4, 5, 7, 12, 17]))
@@ -173,6 +186,8 @@ def test_random_layers_automatic_plan(oracle, seed):
     if layer.K > 2:
         w[int(rng.integers(0, layer.K))] = 0
     check(layer, w, x, oracle, None, what=f"random-{seed}")
+    _, info = check(layer, w, x, oracle, dict(kernel=4), what=f"random-flow-{seed}")
+    assert info["plan"]["kernel"] == 4
 
 
 SHAPES = [
@@ -289,6 +304,7 @@ EPILOGUE_PLANS = [
     dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=3),  # 6 blocks in three parts
     dict(kernel=3, nt=4, cb=3, waves=8, cg=1, rows_w=8, t=3, splits=6),  # one block each
 ]
+EPILOGUE_PLANS += [flow(p) for p in EPILOGUE_PLANS if p and p.get("kernel") == 3]
 
 
 @pytest.mark.parametrize("plan", EPILOGUE_PLANS, ids=[str(i) for i in range(len(EPILOGUE_PLANS))])
@@ -303,10 +319,11 @@ def test_bias_and_relu_epilogue(oracle, plan):
             assert {k: info["plan"][k] for k in plan} == plan
 
 
+@pytest.mark.parametrize("kernel", [3, 4])
 @pytest.mark.parametrize("splits", [2, 5])
-def test_channel_splits_without_epilogue(oracle, splits):
+def test_channel_splits_without_epilogue(oracle, splits, kernel):
     """Partial sums of several workgroups added up by a second launch: the plain entry point, a strip layout, a ragged batch."""
-    plan = dict(kernel=3, nt=4, cb=1, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9, splits=splits)
+    plan = dict(kernel=kernel, nt=4, cb=1, waves=8, cg=1, rows_w=4, t=3, band=7, strip=9, splits=splits)
     x, w = rand_case(BIG, 6, 0.2, seed=73)
     _, info = check(BIG, w, x, oracle, plan, what="splits")
     assert info["plan"]["splits"] == splits

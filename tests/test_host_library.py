@@ -94,6 +94,7 @@ PLANS = [
     dict(kernel=3, nt=4, cb=4, waves=4, cg=1, rows_w=2, t=7, band=8, strip=8),
     dict(kernel=3, nt=4, cb=3, waves=4, cg=1, rows_w=8, t=3, splits=3),          # channel blocks shared by 3 workgroups
 ]
+PLANS += [dict(p, kernel=4) for p in PLANS if p["kernel"] == 3]                   # the flow variant packs the same way
 
 
 @pytest.mark.parametrize("plan", PLANS, ids=[str(i) for i in range(len(PLANS))])
