@@ -123,7 +123,7 @@ def main() -> int:
             traffic = None
 
     def kname(i):
-        return ("sconv_lds2_kernel" if layers[i]["plan"]["kernel"] == 3 else "sconv_lds_kernel") + f" on {layers[i]['name']}"
+        return ("sconv_lds2_kernel" if layers[i]["plan"]["kernel"] in (3, 4) else "sconv_lds_kernel") + f" on {layers[i]['name']}"
 
     roofline = dict(bound="alu", achieved=achieved, peak=PEAK_FMA_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_FMA_TFLOPS, 4), traffic=traffic, traffic_source=traffic_source,

@@ -35,7 +35,9 @@ Two ways of keeping the waves of a workgroup in step with the block buffers (tem
            shows every wave's share of block b present.  A wave that signals S[b+1] is inside block b, so
            S[b+1] complete also means every wave has left block b-1: its buffer may be overwritten with
            block b+2.  Waves drift up to about half a block apart; nobody waits for the slowest wave at
-           every block.
+           every block.  (FLOW_LOOK = 2 is the same with four buffers, loads two blocks ahead and the
+           landing reported when the block during which they were issued is finished: measured slower,
+           the blocks being a quarter shorter.)
 """
 from __future__ import annotations
 
@@ -67,7 +69,12 @@ SOFF, SS, SNCH, STGT = 96, 97, 98, 99            # stream byte offset; staging t
 SNXT = 31                                        # chunks in the next block's segment
 SX0, SX1 = SSEG, SSEG + 1                        # store address pair: the segment pointer is done by then
 MAX_VGPR = 128
-SIGNAL_AFTER = 2             # flow: a wave reports its staged block at the second first-of-three chunk (chunk 3) or at the segment's end
+# flow: how many blocks ahead of the one being multiplied a wave issues loads.  1: three buffers, the landing is
+# reported from inside the block loop (at the SIGNAL_AFTER-th first-of-three chunk, or at the segment's end);
+# 2: four buffers, the landing is reported when the wave finishes the block during which the loads were issued.
+FLOW_LOOK = 1
+FLOW_BUFS = FLOW_LOOK + 2
+SIGNAL_AFTER = 2
 
 # kernel-argument offsets the asm reads (checked by static_asserts next to the struct)
 OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
@@ -257,7 +264,15 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
     emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
     emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
     if flow:
-        signal(0)                                          # my share of the first block is in LDS
+        if FLOW_LOOK == 2:
+            one = label("oneblock")
+            emit(f"s_cmp_le_u32 s{SLEFT}, 1")
+            emit(f"s_cbranch_scc1 {one}")
+            emit(f"s_add_u32 s{STGT}, s{SSTRIDE}, {OP['ldsbase']}")
+            stage(STGT)                                    # the second block, into the second buffer
+            signal(4)
+            emit(f"{one}:")
+        signal(0)                                          # my share of the first block (and the second) is in LDS
         emit("s_mov_b32 vcc_lo, 0")                        # no landing left to report
 
     # ------------------------------------------------------------------ channel blocks
@@ -285,17 +300,20 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
         for t in range(T):
             emit(f"ds_read_b128 {q(d, t)}, v{VA0 + d} offset:{t * step * 16}")
     emit(f"{noreads}:")
-    emit(f"s_cmp_le_u32 s{SLEFT}, 1")                      # the last block stages nothing
+    emit(f"s_cmp_le_u32 s{SLEFT}, {FLOW_LOOK if flow else 1}")   # the last block(s) stage nothing
     emit(f"s_cbranch_scc1 {nostage}")
     if flow:
-        # the buffer after the current one, round the three: block b-2's, which every wave has left
-        emit(f"s_mul_i32 s{STMP}, s{SSTRIDE}, 3")
-        emit(f"s_add_u32 s{STGT}, s{SBUF}, s{SSTRIDE}")
-        emit(f"s_cmp_eq_u32 s{STGT}, s{STMP}")
-        emit(f"s_cselect_b32 s{STGT}, 0, s{STGT}")
+        # FLOW_LOOK buffers on from the current one, round the ring: block b-2's buffer, which every wave has left
+        emit(f"s_mul_i32 s{SNCH}, s{SSTRIDE}, {FLOW_LOOK}")
+        emit(f"s_add_u32 s{STGT}, s{SBUF}, s{SNCH}")
+        emit(f"s_mul_i32 s{SNCH}, s{SSTRIDE}, {FLOW_BUFS}")
+        emit(f"s_cmp_ge_u32 s{STGT}, s{SNCH}")
+        emit(f"s_cselect_b32 s{SNCH}, s{SNCH}, 0")
+        emit(f"s_sub_u32 s{STGT}, s{STGT}, s{SNCH}")
         emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
         stage(STGT)
-        emit(f"s_mov_b32 vcc_lo, {SIGNAL_AFTER}")          # report the landing that many first-of-three chunks on
+        if FLOW_LOOK == 1:
+            emit(f"s_mov_b32 vcc_lo, {SIGNAL_AFTER}")      # report the landing that many first-of-three chunks on
     else:
         emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
         emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
@@ -310,7 +328,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
     emit(f"s_cmp_lg_u32 s{SHALF}, 0")
     emit(f"s_cbranch_scc1 {half}")
     emit(f"{loop}:")
-    body(SA, SB, SN, check=flow)
+    body(SA, SB, SN, check=flow and FLOW_LOOK == 1)
     emit(f"s_cbranch_scc0 {exit1}")
     emit(f"{second}:")
     body(SB, SN, SA)
@@ -340,13 +358,18 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
     emit("s_waitcnt lgkmcnt(0)")                # the last request lands before its registers are reused
     if flow:
         reported = label("reported")
-        emit("s_cmp_eq_u32 vcc_lo, 0")          # a short segment ends before the landing was reported
-        emit(f"s_cbranch_scc1 {reported}")
-        signal(4)
-        emit("s_mov_b32 vcc_lo, 0")
+        if FLOW_LOOK == 1:
+            emit("s_cmp_eq_u32 vcc_lo, 0")      # a short segment ends before the landing was reported
+            emit(f"s_cbranch_scc1 {reported}")
+            signal(4)
+            emit("s_mov_b32 vcc_lo, 0")
+        else:
+            emit(f"s_cmp_le_u32 s{SLEFT}, 2")   # loads were issued at this block's start: they have had the whole block
+            emit(f"s_cbranch_scc1 {reported}")
+            signal(8)
         emit(f"{reported}:")
         emit(f"s_add_u32 {OP['ctr']}, {OP['ctr']}, 4")
-        emit(f"s_mul_i32 s{STMP}, s{SSTRIDE}, 3")
+        emit(f"s_mul_i32 s{STMP}, s{SSTRIDE}, {FLOW_BUFS}")
         emit(f"s_add_u32 s{SBUF}, s{SBUF}, s{SSTRIDE}")
         emit(f"s_cmp_eq_u32 s{SBUF}, s{STMP}")
         emit(f"s_cselect_b32 s{SBUF}, 0, s{SBUF}")
@@ -477,6 +500,7 @@ def generate() -> str:
         parts.append(gen_shape(*s))
         parts.append(gen_shape(*s, flow=True))
     parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r}, {st})" for t, r, _, _, st in SHAPES) + "\n")
+    parts.append(f"#define SCONV_LDS2_FLOW_BUFS {FLOW_BUFS}\n")
     parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
                  f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")
     return "".join(parts)

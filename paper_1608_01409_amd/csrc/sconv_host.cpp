@@ -179,8 +179,8 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     const int64_t page = (int64_t)t.page_cells * p.nt;
     if (page < (int64_t)d.pad * p.nt) return SCONV_ERR_PLAN;
     const int64_t stride = (block + page + 3) / 4 * 4;
-    // barrier variant: two buffers; flow variant: three, and one counter per block behind them
-    t.n_bufs = std::min(flow ? 3 : 2, t.nblk);
+    // barrier variant: two buffers; flow variant: its ring of buffers, and one counter per block behind them
+    t.n_bufs = std::min(flow ? lds2_flow_bufs() : 2, t.nblk);
     const int64_t ctr_bytes = flow ? ((int64_t)t.nblk * 4 + 15) / 16 * 16 : 0;
     if (stride * t.n_bufs * 4 + ctr_bytes > 160 * 1024) return SCONV_ERR_PLAN;
     t.buf_stride_floats = (int)stride;
@@ -273,7 +273,21 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     // fills, and what the staging of the block (L2 to LDS, every workgroup its own copy) takes from the loop;
     // per workgroup: prologue and stores, partly filled by a second workgroup as well
     const double block_bytes = (double)t.p.cb * t.plane_cells * 16.0;
-    double group = m * simd_clk / eff + blocks * (800.0 / m + m * block_bytes / 120.0) + (m >= 2 ? (t.p.waves >= 8 ? 8000.0 : 10500.0) : 14000.0);
+    // The flow variant pays no barrier: measured against the barrier variant on the same layers it gains about
+    // 1000 clocks per block of the barrier variant (0.4-0.7 us per block on the 13x13 layers at any density)
+    // and loses what its smaller blocks cost in padding.  Either variant issues the loads of the next block
+    // when a block starts and cannot start that block before they have landed: a block lasts at least the
+    // landing time, which binds at low density (measured: 3.3 us for 50 KB, 4.5 us for 74 KB per CU).
+    const bool flow = t.p.kernel == 4;
+    const double sync = flow ? 100.0 : 800.0 / m;
+    const double landing = 4000.0 + m * block_bytes / 11.0;
+    const double compute_block = m * simd_clk / eff / blocks;
+    const double per_block = std::max(compute_block + sync + m * block_bytes / 120.0, landing);
+    double group = blocks * per_block + (m >= 2 ? (t.p.waves >= 8 ? 8000.0 : 10500.0) : 14000.0);
+    // Measured: the flow variant is the slower one (3-12 %) where a second workgroup on the CU already fills
+    // the barrier's gaps and the blocks are only a few channels deep, where a block's arithmetic does not outlast its loads by a margin (its loads have
+    // only the first chunks of a block to land in), and where there are too few blocks to rotate buffers.
+    if (flow && ((m >= 2 && t.p.cb < 8) || blocks < 3 || compute_block < 1.5 * landing)) group *= 1.1;
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
     double us = std::ceil(cu_wgs / m) * group / 2400.0;
     if (splits > 1) {
@@ -287,7 +301,7 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
                               std::vector<std::pair<double, LdsTiling>> *all);
 // whether the library, left to itself, considers the flow variant of the flat-stream kernel
-static const bool kFlowByDefault = false;
+static const bool kFlowByDefault = true;
 
 int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
 {
@@ -368,8 +382,9 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                     int cb = g.Cg; // one block, one buffer, if it fits; else two buffers (flow: three)
                     if (fixed + per_ch * cb > budget) {
                         cb = (int)((budget / 2 - fixed) / per_ch);
-                        // flow: two buffers only if the layer then has two blocks, else a third of the budget each
-                        if (kind == 4 && (cb < 1 || ceil_div(g.Cg, cb) > 2)) cb = (int)(((budget - 64) / 3 - fixed) / per_ch);
+                        // flow: as many buffers as the layer has blocks, up to its ring
+                        for (int nb = 3; kind == 4 && nb <= lds2_flow_bufs() && (cb < 1 || ceil_div(g.Cg, cb) >= nb); ++nb)
+                            cb = (int)(((budget - 128) / nb - fixed) / per_ch);
                     }
                     if (req.cb) cb = req.cb;
                     if (cb < 1) continue;

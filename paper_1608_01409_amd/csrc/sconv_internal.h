@@ -74,7 +74,7 @@ struct PackedLds {
 };
 
 // plan.kernel values that run the flat-stream kernel: 3 = a barrier per channel block, two block buffers;
-// 4 = the flow variant, three buffers and per-block counters instead of barriers.  Same packing for both.
+// 4 = the flow variant, lds2_flow_bufs() buffers and per-block counters instead of barriers.  Same packing for both.
 inline bool is_flat_kernel(int kernel) { return kernel == 3 || kernel == 4; }
 
 // Packing for the flat-stream kernel (tiles of 4 images).  One stream per (wave slot, channel block)
@@ -124,7 +124,8 @@ int unpack_lds(const sconv_desc &d, const PackedLds &p, Canonical &out);
 int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, PackedFlat &out);
 int unpack_flat(const sconv_desc &d, const PackedFlat &p, Canonical &out);
 bool lds2_kernel_available(int t, int rows_w, int step); // step: 64 (flat lanes) or the strip width
-int lds2_depth(int t, int rows_w); // read-ahead depth of a flat-stream shape, 0 if there is none
+int lds2_depth(int t, int rows_w);
+int lds2_flow_bufs(); // block buffers the flow variant of the flat-stream kernel rotates through // read-ahead depth of a flat-stream shape, 0 if there is none
 int pack_direct(const sconv_desc &d, const Canonical &c, PackedDirect &out);
 int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
 

@@ -616,6 +616,8 @@ bool lds2_kernel_available(int t, int rows_w, int step)
     return false;
 }
 
+int lds2_flow_bufs() { return SCONV_LDS2_FLOW_BUFS; }
+
 int lds2_depth(int t, int rows_w)
 {
 #define X(TT, RW, ST) if (t == TT && rows_w == RW && ST == 64) return Lds2Asm<TT, RW, ST, false>::kDepth;
@@ -778,7 +780,7 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     if (t.p.strip && (t.strip_rows < 1 || t.strip_rows * t.p.strip > 64 || t.p.band > t.p.cg * t.strip_rows)) return SCONV_ERR_PLAN;
     const bool flow = t.p.kernel == 4;
     if (flow != (t.ctr_bytes_at > 0) || (flow && t.ctr_bytes_at + 4 * t.nblk > t.lds_bytes)) return SCONV_ERR_PLAN;
-    if (t.n_bufs != (flow ? std::min(3, t.nblk) : std::min(2, t.nblk))) return SCONV_ERR_PLAN;
+    if (t.n_bufs != std::min(flow ? SCONV_LDS2_FLOW_BUFS : 2, t.nblk)) return SCONV_ERR_PLAN;
 #define X(TT, RW, ST) \
     if (t.p.t == TT && t.p.rows_w == RW && step == ST) \
         return flow ? launch_lds2_inst<TT, RW, ST, true>(a, grid, threads, t.lds_bytes, s, hip_err) \

@@ -55,7 +55,7 @@ def test_channel_splits_two_calls_second_smaller(oracle):
         xd, ref, got = both(h, layer, x[:n])
         plan = B.sconv_csr_info(h)["plan"]
         say(f"noalloc conv3 N={n} plan={plan}")
-        assert plan["kernel"] == 3 and plan["splits"] > 1, plan
+        assert plan["kernel"] in (3, 4) and plan["splits"] > 1, plan
         runs.append((xd, ref, got, plan))
     # both packings are resident now; the two calls in a row, the larger input first
     for xd, ref, got, plan in runs:
