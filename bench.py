@@ -30,9 +30,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tune", type=int, default=0,
+    ap.add_argument("--tune", type=int, default=8,
                     help="during set-up let sconv_tune time this many candidate tilings per layer and keep the "
-                         "fastest (0: the cost model's choice)")
+                         "fastest, as a deployment of the library would (0: the cost model's choice, untimed)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for "
                          "scaling the HBM byte counters of a profiler run)")
@@ -133,15 +133,30 @@ def main() -> int:
                     frac_of_published_fp32_vector=round(achieved / PEAK_FP32_PUBLISHED_TFLOPS, 4),
                     step_frac=round(value / 1e3 / PEAK_FMA_TFLOPS, 4), per_layer=per_layer)
 
+    # how steady the timed region was: the GPU's power management settles over the first tens of milliseconds
+    # of load, and steps taken during that time run up to 15 % slower than later ones
+    step_us = [ev[k][0][0].elapsed_time(ev[k][-1][1]) * 1e3 for k in range(args.steps)]
+    q = max(1, args.steps // 4)
+    steadiness = dict(first_quarter_us=round(float(np.mean(step_us[:q])), 1), last_quarter_us=round(float(np.mean(step_us[-q:])), 1))
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import sconv_oracle as O
         t_cpu, used, reps = 0.0, 0, 0
         csr = []
+        checked = []
         for L in layers:
             x, w = L["host"]
             rp, ci, v = O.csr_from_dense(L["layer"], w)
             csr.append((rp, O.lower_offsets(L["layer"], rp, ci), v))
+            # what the timed steps left in the output buffers, against the fp64 oracle on sampled images
+            idx = sorted({0, L["N"] // 3, (2 * L["N"]) // 3, L["N"] - 1})
+            ref, ab = O.forward_f64(L["layer"], rp, csr[-1][1], v, x[idx])
+            got = L["out"][idx].cpu().numpy().astype(np.float64)
+            if not np.all(np.abs(got - ref) <= 1e-5 * ab):
+                print(f"bench.py: {L['name']} does not match the oracle with tiling {L['plan']}", file=sys.stderr)
+                return 3
+            checked.append(f"{L['name']}: images {idx}")
         while t_cpu < 10.0 and reps < 20:
             for L, (rp, off, v) in zip(layers, csr):
                 a = time.perf_counter()
@@ -149,7 +164,8 @@ def main() -> int:
                 t_cpu += time.perf_counter() - a
             reps += 1
         cpu = dict(value=round(total_flops * reps / t_cpu / 1e9, 2), unit="GFLOP/s", cores=used, kind="oracle",
-                   sample=f"the whole step (conv2-5, batch 256) x {reps} repetitions, fp32 loop of Figure 2, OpenMP")
+                   sample=f"the whole step (conv2-5, batch 256) x {reps} repetitions, fp32 loop of Figure 2, OpenMP",
+                   gpu_outputs_checked="the timed steps' outputs within 1e-5 * sum|w*x| of the fp64 oracle on " + "; ".join(checked))
 
     print(json.dumps({
         "metric": "effective GFLOP/s (2*nnz*OH*OW*N/s), AlexNet conv2-5 @ 10% density",
@@ -157,7 +173,8 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "AlexNet conv2-conv5, batch 256, fp32, Bernoulli masks at density 0.10", "global_batch": 256,
-                   "tiling": f"fastest of {args.tune} candidates timed during set-up" if args.tune > 0 else "cost model",
+                   "tiling": f"fastest of {args.tune} candidates timed during set-up (sconv_tune)" if args.tune > 0 else "cost model",
+                   "timed_region": steadiness,
                    "dense_equivalent_gflops": round(sum(L["dense_flops"] for L in layers) / (ms_per_step * 1e-3) / 1e9, 1)},
         "roofline": roofline, "cpu_baseline": cpu}))
     return 0

@@ -211,6 +211,25 @@ __global__ void __launch_bounds__(1024) sconv_lds_kernel(const LdsArgs a)
 //     blocks, stores) runs inside one asm statement that owns a fixed block of registers;
 //   * staging uses buffer loads into LDS whose range check returns 0 for the padding cells, so no
 //     part of a plane is ever cleared and every cell of a block is rewritten with each block.
+// Division of a small non-negative number by a divisor fixed per launch: a multiply-high with
+// magic = ceil(2^32 / d), exact while n * d < 2^32 (the launcher checks the largest n of each use and passes
+// magic = 0, meaning "divide", where that does not hold or d is 1).  The generic 32-bit division costs some 30
+// instructions per use, and the kernel's first microsecond was mostly these.
+struct FastDiv {
+    unsigned d, magic;
+};
+static __device__ __forceinline__ int fdiv(int n, FastDiv f)
+{
+    return f.magic ? (int)__umulhi((unsigned)n, f.magic) : n / (int)f.d;
+}
+static FastDiv make_fastdiv(int d, int64_t n_max)
+{
+    FastDiv f;
+    f.d = (unsigned)d;
+    f.magic = (d > 1 && n_max * (int64_t)d < ((int64_t)1 << 32)) ? (unsigned)((((uint64_t)1 << 32) + d - 1) / (uint64_t)d) : 0u;
+    return f;
+}
+
 struct Lds2Args {
     const float *in;
     float *out;
@@ -236,6 +255,7 @@ struct Lds2Args {
     const float *bias;       // [K] added to every output of row k, or null
     int relu;                // outputs below zero become zero
     int ctr_bytes_at;        // flow: LDS byte offset of the per-block landing counters (one dword per block)
+    FastDiv d_units, d_splits, d_bands, d_nkt, d_cg, d_wl, d_strip; // the divisors of the index arithmetic below
 };
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -268,24 +288,26 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     int unit, tile;
     if (bid < full) {
         const int xcd = bid & 7, slot = bid >> 3;
-        unit = slot % a.units;
-        tile = (slot / a.units) * 8 + xcd;
+        const int q = fdiv(slot, a.d_units);
+        unit = slot - q * a.units;
+        tile = q * 8 + xcd;
     } else {
         const int j = bid - full;
-        tile = (a.n_tiles >> 3) * 8 + j / a.units;
-        unit = j % a.units;
+        const int q = fdiv(j, a.d_units);
+        tile = (a.n_tiles >> 3) * 8 + q;
+        unit = j - q * a.units;
     }
     if (tile >= a.n_tiles) return;
-    const int us = unit / a.splits, split = unit - us * a.splits;
-    const int gk = us / a.n_bands, band_i = us - gk * a.n_bands;
-    const int g = gk / a.nkt, kt = gk - g * a.nkt;
+    const int us = fdiv(unit, a.d_splits), split = unit - us * a.splits;
+    const int gk = fdiv(us, a.d_bands), band_i = us - gk * a.n_bands;
+    const int g = fdiv(gk, a.d_nkt), kt = gk - g * a.nkt;
     const int n0 = tile * 4;
     const int y0 = band_i * a.band;
     const int blk0 = split * a.blk_split;                                 // first channel block of this workgroup
     const int nblk_here = min(a.blk_split, a.nblk - blk0);
     if (nblk_here <= 0) return; // the host never launches an empty part; the block loop needs one block at least
     const int ch0 = blk0 * a.cb, nch_here = min(nblk_here * a.cb, a.Cg - ch0);
-    const int rgi = __builtin_amdgcn_readfirstlane(wave / a.cg);
+    const int rgi = __builtin_amdgcn_readfirstlane(fdiv(wave, a.d_cg));
     const int cgi = wave - rgi * a.cg;
     const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
     const int nimg = min(4, a.N - n0);
@@ -296,7 +318,7 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     for (int j = 0; j < 4; ++j) {
         const int f = (wave + j * n_waves) * 64 + lane;
         const int cell = f >> 2, img = f & 3;
-        const int Y = cell / a.Wl, X = cell - Y * a.Wl;
+        const int Y = fdiv(cell, a.d_wl), X = cell - Y * a.Wl;
         const int iy = y0 + Y - a.pad, ix = X - a.pad;
         const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
         voff[j] = f >= a.plane_floats ? kSkipLane
@@ -349,7 +371,7 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     // read of the wave a bank conflict with the lane that owns that bank).
     int cell0 = cgi * T * 64 + lane;
     if (STEP != 64) {
-        const int by = lane / a.strip, bx = lane - by * a.strip;
+        const int by = fdiv(lane, a.d_strip), bx = lane - by * a.strip;
         const int y = cgi * a.strip_rows + by;
         cell0 = y * a.Wl + bx;
         if (by >= a.strip_rows || y >= a.band) cell0 &= 15;
@@ -775,6 +797,14 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     const int64_t grid64 = (int64_t)a.n_tiles * a.units;
     if (grid64 > 0x7fffffff) return SCONV_ERR_RANGE;
     const int grid = (int)grid64, threads = t.p.waves * 64;
+    // the largest dividend of each division in the kernel's index arithmetic
+    a.d_units = make_fastdiv(a.units, grid64);
+    a.d_splits = make_fastdiv(a.splits, a.units);
+    a.d_bands = make_fastdiv(a.n_bands, a.units);
+    a.d_nkt = make_fastdiv(a.nkt, a.units);
+    a.d_cg = make_fastdiv(a.cg, 16);
+    a.d_wl = make_fastdiv(a.Wl, (int64_t)4 * threads * 64);     // cells of the slabs a workgroup can stage
+    a.d_strip = make_fastdiv(std::max(1, a.strip), 64);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int step = t.p.strip ? t.p.strip : 64;
     if (t.p.strip && (t.strip_rows < 1 || t.strip_rows * t.p.strip > 64 || t.p.band > t.p.cg * t.strip_rows)) return SCONV_ERR_PLAN;
