@@ -36,6 +36,9 @@ def main() -> int:
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for "
                          "scaling the HBM byte counters of a profiler run)")
+    ap.add_argument("--dispatch-log", default="",
+                    help="write the order of the forward calls of the warm-up and timed steps here (JSON), for "
+                         "profile_summary.py to attribute a profiler's dispatches to layers")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards over the batch with no exchange "
@@ -96,6 +99,16 @@ def main() -> int:
         step(ev[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    if args.dispatch_log:
+        def n_kernels(L):
+            return 1 + (1 if L["plan"]["splits"] > 1 else 0) + (1 if L["layer"].stride > 1 and L["plan"]["kernel"] != 2 else 0)
+        calls = [dict(layer=L["name"], kernels=n_kernels(L), phase=ph) for ph, n in (("warmup", args.warmup), ("timed", args.steps))
+                 for _ in range(n) for L in layers]
+        json.dump(dict(config="bench.py: AlexNet conv2-5, batch 256, density 0.10" + (f", tilings tuned (--tune {args.tune})" if args.tune > 0 else ""),
+                       copy_probe_mb=args.copy_probe_mb,
+                       layers=[dict(name=L["name"], plan=L["plan"], N=L["N"], flops=L["flops"], kernels=n_kernels(L),
+                                    bytes=4.0 * L["N"] * (L["layer"].C * L["layer"].H * L["layer"].W + L["layer"].K * L["layer"].OH * L["layer"].OW) + 8.0 * L["nnz"])
+                               for L in layers], calls=calls), open(args.dispatch_log, "w"))
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     total_flops = sum(L["flops"] for L in layers)
     value = total_flops / (ms_per_step * 1e-3) / 1e9

@@ -4,7 +4,8 @@
 //   v_fma_f32 rate            16 independent accumulators, SGPR multiplier
 //   ds_read_b128 bandwidth    8 aligned reads in flight per wave
 //   the inner loop's mix      4 v_fmac_f32 per ds_read_b128 (+ address add, + scalar work), see gen_ceilings.py
-//   device copy bandwidth     float4 copy of 1 GiB
+//   device copy bandwidth     float4 copy of 1 GiB; read alone and write alone over the same gigabyte
+//   L2 read bandwidth         every workgroup reads the same 1 MiB over and over (it stays in each XCD's L2)
 // All LDS addresses stay inside the 64 KB static array: lane*16 + (wave & 3)*1024 + offset (< 30.5 KB)
 // + 2*1024 + 16.
 #include <hip/hip_runtime.h>
@@ -59,6 +60,35 @@ __global__ void __launch_bounds__(1024) k_mix(float *out, int iters)
 __global__ void __launch_bounds__(256) k_copy(const float4 *src, float4 *dst, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+// sum of what is read, so the loads cannot be dropped; n float4s, grid-stride
+__global__ void __launch_bounds__(256) k_read(const float4 *src, float *out, size_t n)
+{
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float4 v = src[i];
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) out[0] = acc.x;
+}
+
+__global__ void __launch_bounds__(256) k_write(float4 *dst, size_t n)
+{
+    const float4 v = make_float4(1.f, 2.f, 3.f, 4.f);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = v;
+}
+
+// every workgroup walks the same `n` float4s `reps` times: after the first pass they come from L2
+__global__ void __launch_bounds__(256) k_read_l2(const float4 *src, float *out, int n, int reps)
+{
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = 0; r < reps; ++r)
+        for (int i = threadIdx.x; i < n; i += 256) {
+            const float4 v = src[(i + r * 64) % n];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) out[0] = acc.x;
 }
 
 template <class F>
@@ -119,6 +149,16 @@ int main()
     float ms;
     if (time_ms([&] { hipLaunchKernelGGL(k_copy, dim3(kCUs * 8), dim3(256), 0, 0, a, b, bytes / 16); }, &ms)) return 1;
     printf("device copy  1 GiB: %.3f ms, %.2f TB/s (read + write)\n", ms, 2.0 * bytes / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(k_read, dim3(kCUs * 8), dim3(256), 0, 0, a, dout, bytes / 16); }, &ms)) return 1;
+    printf("HBM read     1 GiB: %.3f ms, %.2f TB/s\n", ms, 1.0 * bytes / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(k_write, dim3(kCUs * 8), dim3(256), 0, 0, b, bytes / 16); }, &ms)) return 1;
+    printf("HBM write    1 GiB: %.3f ms, %.2f TB/s\n", ms, 1.0 * bytes / ms / 1e9);
+    {
+        const int n = (1 << 20) / 16, reps = 64, wgs = kCUs * 8;
+        if (time_ms([&] { hipLaunchKernelGGL(k_read_l2, dim3(wgs), dim3(256), 0, 0, a, dout, n, reps); }, &ms)) return 1;
+        printf("L2 read      1 MiB per workgroup x %d, %d workgroups: %.3f ms, %.2f TB/s\n", reps, wgs, ms,
+               (double)wgs * reps * (1 << 20) / ms / 1e9);
+    }
     CK(hipFree(a));
     CK(hipFree(b));
     CK(hipFree(dout));

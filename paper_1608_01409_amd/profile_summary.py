@@ -1,16 +1,17 @@
 #!/usr/bin/env python3
-"""Turn raw rocprofv3 output of bench.py runs into the short text summaries kept
-under profiles/ and into profiles/hbm_traffic.json (HBM bytes per launch of each
+"""Turn raw rocprofv3 output of profile_run.py (or bench.py) runs into the short text summaries kept under
+profiles/, and, for the alexnet configuration, into profiles/hbm_traffic.json (HBM bytes per launch of each
 layer's kernel, which bench.py reports as roofline.traffic).
 
-    python -m paper_1608_01409_amd.profile_summary RAW_DIR OUT_DIR
+    python -m paper_1608_01409_amd.profile_summary RAW_DIR OUT_FILE [--traffic-json PATH]
 
-RAW_DIR holds one sub-directory per profiler run, named as in the header of the
-kernel summary under profiles/: kt (kernel trace + stats), fetch (FETCH_SIZE),
-write (WRITE_SIZE), sq1, sq2 (SQ counters), l2 (TCC request counters).  The byte
-counters and the L2 request counters are scaled by what the same counter reads
-for the plain device copy bench.py launches with --copy-probe-mb (a kernel that
-moves a known number of bytes each way).
+RAW_DIR holds one sub-directory per profiler run: kt (kernel trace), fetch (FETCH_SIZE), write (WRITE_SIZE),
+sq1, sq2 (SQ counters), l2 (TCC request counters), each with the profiler's CSV files and the log.json that
+profile_run.py wrote for that run (which forward call launched which dispatches).  Dispatches are attributed to
+layers from the end of the run backwards, so launches that precede the log (library set-up) do not matter.  The
+byte counters and the L2 request counters are scaled by what the same counter reads for the plain device copy
+of --copy-probe-mb (a kernel that moves a known number of bytes each way).  Rates are set beside the ceilings
+of profiles/ceilings_gfx950.txt.
 """
 from __future__ import annotations
 
@@ -21,8 +22,8 @@ import os
 import sys
 from collections import defaultdict
 
-LAYERS = ["conv2", "conv3", "conv4", "conv5"]
-COPY_MB = 256
+MAIN = ("sconv_lds2_kernel", "sconv_lds_kernel", "sconv_direct_kernel")
+CEIL = dict(fma_lanes=59.0, lds_b_clk=253.7, copy_tbs=4.83, l2_read_tbs=34.5)   # per CU per clock; whole chip
 
 
 def find(raw, run, suffix):
@@ -30,101 +31,166 @@ def find(raw, run, suffix):
     return hits[0] if hits else None
 
 
-def counters(raw, run):
-    """{counter: {"layers": {layer: mean per launch}, "copy": value}} for one --pmc run."""
-    path = find(raw, run, "counter_collection.csv")
-    if not path:
-        return {}
-    rows = list(csv.DictReader(open(path)))
-    per = defaultdict(lambda: defaultdict(list))   # counter -> dispatch -> values
-    name = {}
-    for r in rows:
-        d = int(r["Dispatch_Id"])
-        per[r["Counter_Name"]][d].append(float(r["Counter_Value"]))
-        name[d] = r["Kernel_Name"]
-    sconv = sorted(d for d, n in name.items() if "sconv_lds" in n or "sconv_direct" in n)
-    copies = sorted(d for d, n in name.items() if "copy" in n.lower() or "elementwise" in n.lower())
+def load_log(raw, run):
+    p = os.path.join(raw, run, "log.json")
+    return json.load(open(p)) if os.path.exists(p) else None
+
+
+def attribute(dispatches, log):
+    """dispatches: [(id, kernel name)] in launch order.  Returns {id: (layer, phase, role)} for the library's
+    kernels, matched to the log's calls from the end backwards; role = main / aux (phase images, reduction)."""
+    ours = [(d, n) for d, n in dispatches if "sconv" in n]
     out = {}
-    for c, by_d in per.items():
-        lay = defaultdict(list)
-        for i, d in enumerate(sconv):
-            lay[LAYERS[i % len(LAYERS)]].append(sum(by_d.get(d, [0.0])))
-        # the probe copy is the largest copy-like dispatch
-        cp = max((sum(by_d.get(d, [0.0])) for d in copies), default=None)
-        out[c] = {"layers": {k: sum(v) / len(v) for k, v in lay.items()}, "copy": cp, "launches": len(sconv)}
+    i = len(ours)
+    for call in reversed(log["calls"]):
+        k = call["kernels"]
+        if i - k < 0:
+            break
+        for d, n in ours[i - k:i]:
+            out[d] = (call["layer"], call["phase"], "main" if any(m in n for m in MAIN) else "aux")
+        i -= k
     return out
 
 
+def counters(raw, run):
+    """({counter: {layer: mean per timed forward call, main kernel + aux}}, {counter: copy value}, log)"""
+    path, log = find(raw, run, "counter_collection.csv"), load_log(raw, run)
+    if not path or not log:
+        return {}, {}, log
+    per = defaultdict(lambda: defaultdict(float))   # counter -> dispatch -> value (summed over instances)
+    name = {}
+    for r in csv.DictReader(open(path)):
+        d = int(r["Dispatch_Id"])
+        per[r["Counter_Name"]][d] += float(r["Counter_Value"])
+        name[d] = r["Kernel_Name"]
+    order = sorted(name)
+    who = attribute([(d, name[d]) for d in order], log)
+    copies = [d for d in order if "sconv" not in name[d] and ("copy" in name[d].lower() or "elementwise" in name[d].lower())]
+    n_timed = defaultdict(int)
+    for c in log["calls"]:
+        if c["phase"] == "timed":
+            n_timed[c["layer"]] += 1
+    out, cp = {}, {}
+    for c, by_d in per.items():
+        lay = defaultdict(float)
+        for d, (layer, phase, role) in who.items():
+            if phase == "timed":
+                lay[layer] += by_d.get(d, 0.0)
+        out[c] = {l: v / max(1, n_timed[l]) for l, v in lay.items()}
+        cp[c] = max((by_d.get(d, 0.0) for d in copies), default=None)
+    return out, cp, log
+
+
+def kernel_times(raw):
+    path, log = find(raw, "kt", "kernel_trace.csv"), load_log(raw, "kt")
+    if not path or not log:
+        return None, log
+    rows = sorted(((int(r["Dispatch_Id"]), r["Kernel_Name"], int(r["Start_Timestamp"]), int(r["End_Timestamp"]))
+                   for r in csv.DictReader(open(path))), key=lambda r: r[0])
+    who = attribute([(d, n) for d, n, _, _ in rows], log)
+    by = defaultdict(lambda: defaultdict(list))      # layer -> kernel name -> durations (timed phase)
+    for d, n, t0, t1 in rows:
+        if d in who and who[d][1] == "timed":
+            by[who[d][0]][n].append((t1 - t0) / 1e3)
+    return by, log
+
+
 def main() -> int:
-    raw, out_dir = sys.argv[1], sys.argv[2]
-    os.makedirs(out_dir, exist_ok=True)
+    args = [a for a in sys.argv[1:] if not a.startswith("--")]
+    raw, out_file = args[0], args[1]
+    traffic_json = None
+    if "--traffic-json" in sys.argv:
+        traffic_json = sys.argv[sys.argv.index("--traffic-json") + 1]
     lines = []
-    kt = find(raw, "kt", "kernel_stats.csv")
-    if kt:
-        lines.append("kernel trace (rocprofv3 --kernel-trace --stats), all launches of bench.py's run")
-        lines.append(f"{'kernel':70s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}")
-        for r in csv.DictReader(open(kt)):
-            lines.append(f"{r['Name'][:70]:70s} {r['Calls']:>6s} {float(r['AverageNs'])/1e3:9.2f} "
-                         f"{float(r['MinNs'])/1e3:9.2f} {float(r['MaxNs'])/1e3:9.2f} {float(r['Percentage']):6.2f}")
+    by, log = kernel_times(raw)
+    if not log:
+        print("no kt/log.json under", raw, file=sys.stderr)
+        return 2
+    layers = [L["name"] for L in log["layers"]]
+    meta = {L["name"]: L for L in log["layers"]}
+    copy_mb = None
+    lines.append(f"configuration: {log['config']}; tilings in use:")
+    for l in layers:
+        p = meta[l]["plan"]
+        lines.append(f"  {l:16s} N {meta[l]['N']:4d}  kernel {p['kernel']} cb {p['cb']} waves {p['waves']} cg {p['cg']} rows_w {p['rows_w']} t {p['t']} "
+                     f"band {p['band']} strip {p['strip']} splits {p['splits']};  {meta[l]['flops'] / 1e9:.2f} GFLOP (nonzeros only), "
+                     f"{meta[l]['bytes'] / 1e6:.1f} MB algorithmic HBM bytes per launch")
+    lines.append("")
+    kt_main = {}
+    if by:
+        lines.append("kernel trace (rocprofv3 --kernel-trace), timed launches only, per layer in launch order")
+        lines.append(f"  {'layer':16s} {'kernel':62s} {'calls':>5s} {'avg_us':>8s} {'min_us':>8s} {'max_us':>8s} {'TFLOP/s':>8s} {'of 78.6':>7s}")
+        for l in layers:
+            for n, ds in by.get(l, {}).items():
+                is_main = any(m in n for m in MAIN)
+                avg = sum(ds) / len(ds)
+                if is_main:
+                    kt_main[l] = avg
+                tf = meta[l]["flops"] / avg / 1e6 if is_main else 0.0
+                lines.append(f"  {l:16s} {n.replace('void sconv::', '')[:62]:62s} {len(ds):5d} {avg:8.2f} {min(ds):8.2f} {max(ds):8.2f} "
+                             + (f"{tf:8.2f} {tf / 78.6:7.1%}" if is_main else f"{'':8s} {'':7s}"))
         lines.append("")
     traffic = {}
-    fetch, write = counters(raw, "fetch").get("FETCH_SIZE"), counters(raw, "write").get("WRITE_SIZE")
-    if fetch and write and fetch["copy"] and write["copy"]:
-        expect_kib = COPY_MB * 1024.0
-        fs, ws = expect_kib / fetch["copy"], expect_kib / write["copy"]
-        lines.append(f"HBM traffic per launch (FETCH_SIZE / WRITE_SIZE, KiB; scale factors from a {COPY_MB} MiB copy: "
-                     f"read x{fs:.3f}, write x{ws:.3f})")
-        for l in LAYERS:
-            rd = fetch["layers"].get(l, 0.0) * fs * 1024.0
-            wr = write["layers"].get(l, 0.0) * ws * 1024.0
+    fetch, fcopy, flog = counters(raw, "fetch")
+    write, wcopy, _ = counters(raw, "write")
+    if fetch.get("FETCH_SIZE") and write.get("WRITE_SIZE") and fcopy.get("FETCH_SIZE") and wcopy.get("WRITE_SIZE"):
+        copy_mb = flog["copy_probe_mb"]
+        expect_kib = copy_mb * 1024.0
+        fs, ws = expect_kib / fcopy["FETCH_SIZE"], expect_kib / wcopy["WRITE_SIZE"]
+        lines.append(f"HBM traffic per launch (FETCH_SIZE / WRITE_SIZE, KiB; scale factors from a {copy_mb} MiB copy: "
+                     f"read x{fs:.3f}, write x{ws:.3f}); 'x alg' = measured / algorithmic bytes")
+        for l in layers:
+            rd = fetch["FETCH_SIZE"].get(l, 0.0) * fs * 1024.0
+            wr = write["WRITE_SIZE"].get(l, 0.0) * ws * 1024.0
             traffic[l] = {"read_bytes": round(rd), "write_bytes": round(wr), "bytes": round(rd + wr)}
-            lines.append(f"  {l}: read {rd/1e6:8.1f} MB  write {wr/1e6:8.1f} MB")
+            lines.append(f"  {l:16s} read {rd / 1e6:8.1f} MB  write {wr / 1e6:8.1f} MB  x alg {(rd + wr) / meta[l]['bytes']:.2f}")
         lines.append("")
-        json.dump(traffic, open(os.path.join(out_dir, "hbm_traffic.json"), "w"), indent=1)
-    for run in ("sq1", "sq2"):
-        cs = counters(raw, run)
+        if traffic_json:
+            json.dump(traffic, open(traffic_json, "w"), indent=1)
+    sq1, _, _ = counters(raw, "sq1")
+    sq2, _, _ = counters(raw, "sq2")
+    for tag, cs in (("sq1", sq1), ("sq2", sq2)):
         if cs:
-            lines.append(f"SQ counters per launch ({run})")
+            lines.append(f"SQ counters per launch ({tag})")
             for c in sorted(cs):
-                lines.append(f"  {c:28s} " + "  ".join(f"{l} {cs[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
+                lines.append(f"  {c:26s} " + "  ".join(f"{l} {cs[c].get(l, 0):.4g}" for l in layers))
             lines.append("")
-    l2 = counters(raw, "l2")
-    l2_read_bytes = {}
-    if l2 and "TCC_READ_sum" in l2 and l2["TCC_READ_sum"]["copy"]:
-        per_req = COPY_MB * 2.0 ** 20 / l2["TCC_READ_sum"]["copy"]
-        lines.append(f"L2 (TCC) counters per launch; one read request = {per_req:.1f} B (from the {COPY_MB} MiB copy)")
+    l2, l2copy, l2log = counters(raw, "l2")
+    l2_read = {}
+    if l2.get("TCC_READ_sum") and l2copy.get("TCC_READ_sum"):
+        per_req = l2log["copy_probe_mb"] * 2.0 ** 20 / l2copy["TCC_READ_sum"]
+        lines.append(f"L2 (TCC) counters per launch; one read request = {per_req:.1f} B (from the {l2log['copy_probe_mb']} MiB copy)")
         for c in sorted(l2):
-            lines.append(f"  {c:28s} " + "  ".join(f"{l} {l2[c]['layers'].get(l, 0):.4g}" for l in LAYERS))
-        for l in LAYERS:
-            l2_read_bytes[l] = l2["TCC_READ_sum"]["layers"].get(l, 0.0) * per_req
+            lines.append(f"  {c:26s} " + "  ".join(f"{l} {l2[c].get(l, 0):.4g}" for l in layers))
+        for l in layers:
+            l2_read[l] = l2["TCC_READ_sum"].get(l, 0.0) * per_req
         if "TCC_HIT_sum" in l2 and "TCC_MISS_sum" in l2:
-            hr = {l: l2["TCC_HIT_sum"]["layers"].get(l, 0.0) /
-                  max(1.0, l2["TCC_HIT_sum"]["layers"].get(l, 0.0) + l2["TCC_MISS_sum"]["layers"].get(l, 0.0)) for l in LAYERS}
-            lines.append("  hit rate                     " + "  ".join(f"{l} {hr[l]:.1%}" for l in LAYERS))
+            lines.append("  hit rate                   " + "  ".join(
+                f"{l} {l2['TCC_HIT_sum'].get(l, 0.0) / max(1.0, l2['TCC_HIT_sum'].get(l, 0.0) + l2['TCC_MISS_sum'].get(l, 0.0)):.1%}" for l in layers))
         lines.append("")
-    # rates derived from the counters, beside the ceilings measured by the microbenchmark
-    # (`paper_1608_01409_amd/sconv_ceilings`: v_fma_f32 60 lanes-FMA/clk/CU, ds_read_b128 242 B/clk/CU, copy 4.9 TB/s)
-    sq1, sq2 = counters(raw, "sq1"), counters(raw, "sq2")
     if sq1 and sq2 and "GRBM_GUI_ACTIVE" in sq1:
-        lines.append("derived per layer (kernel cycles = GRBM_GUI_ACTIVE / 8 XCDs; SQ instruction counters are per wave, "
-                     "x64 lanes; one LDS instruction of this kernel moves 1 KiB)")
-        lines.append(f"  {'layer':6s} {'us@2.4GHz':>10s} {'FMA lanes/clk/CU':>17s} {'of 64':>6s} {'LDS B/clk/CU':>13s} {'VALU busy':>10s} "
-                     f"{'HBM TB/s':>9s} {'L2 read TB/s':>13s} {'bank conflict cyc':>18s}")
-        for l in LAYERS:
-            cyc = sq1["GRBM_GUI_ACTIVE"]["layers"].get(l, 0.0) / 8.0
+        lines.append("derived per layer, each beside its ceiling (kernel cycles = GRBM_GUI_ACTIVE / 8 XCDs; SQ instruction counters "
+                     "are per wave, x 64 lanes; one LDS instruction of these kernels moves 1 KiB)")
+        lines.append(f"  ceilings (profiles/ceilings_gfx950.txt): v_fma_f32 {CEIL['fma_lanes']} lanes-FMA/clk/CU of 64, ds_read_b128 "
+                     f"{CEIL['lds_b_clk']} B/clk/CU, device copy {CEIL['copy_tbs']} TB/s, L2 read {CEIL['l2_read_tbs']} TB/s")
+        lines.append(f"  {'layer':16s} {'us@2.4GHz':>10s} {'FMA lanes/clk/CU':>17s} {'of 64':>6s} {'LDS B/clk/CU':>13s} {'of peak':>8s} {'VALU busy':>10s} "
+                     f"{'HBM TB/s':>9s} {'of copy':>8s} {'L2 read TB/s':>13s} {'of peak':>8s} {'bank confl':>10s}")
+        for l in layers:
+            cyc = sq1["GRBM_GUI_ACTIVE"].get(l, 0.0) / 8.0
             if cyc <= 0:
                 continue
-            fma = sq2.get("SQ_INSTS_VALU_FMA_F32", {"layers": {}})["layers"].get(l, 0.0) * 64.0 / (cyc * 256.0)
-            lds = sq2.get("SQ_INSTS_LDS", {"layers": {}})["layers"].get(l, 0.0) * 1024.0 / (cyc * 256.0)
-            busy = sq1.get("SQ_ACTIVE_INST_VALU", {"layers": {}})["layers"].get(l, 0.0) * 4.0 / (cyc * 1024.0)
+            fma = sq2.get("SQ_INSTS_VALU_FMA_F32", {}).get(l, 0.0) * 64.0 / (cyc * 256.0)
+            lds = sq2.get("SQ_INSTS_LDS", {}).get(l, 0.0) * 1024.0 / (cyc * 256.0)
+            busy = sq1.get("SQ_ACTIVE_INST_VALU", {}).get(l, 0.0) * 4.0 / (cyc * 1024.0)
             hbm = traffic.get(l, {}).get("bytes", 0) / (cyc / 2.4e9) / 1e12 if traffic else 0.0
-            bc = sq2.get("SQ_LDS_BANK_CONFLICT", {"layers": {}})["layers"].get(l, 0.0)
-            l2bw = l2_read_bytes.get(l, 0.0) / (cyc / 2.4e9) / 1e12
-            lines.append(f"  {l:6s} {cyc/2.4e3:10.1f} {fma:17.2f} {fma/64:6.1%} {lds:13.1f} {busy:10.1%} {hbm:9.2f} {l2bw:13.2f} {bc:18.0f}")
+            bc = sq2.get("SQ_LDS_BANK_CONFLICT", {}).get(l, 0.0)
+            l2bw = l2_read.get(l, 0.0) / (cyc / 2.4e9) / 1e12
+            lines.append(f"  {l:16s} {cyc / 2.4e3:10.1f} {fma:17.2f} {fma / 64:6.1%} {lds:13.1f} {lds / CEIL['lds_b_clk']:8.1%} {busy:10.1%} "
+                         f"{hbm:9.2f} {hbm / CEIL['copy_tbs']:8.1%} {l2bw:13.2f} {l2bw / CEIL['l2_read_tbs']:8.1%} {bc:10.0f}")
         lines.append("")
     text = "\n".join(lines)
     print(text)
-    open(os.path.join(out_dir, "_summary_body.txt"), "w").write(text)
+    open(out_file, "w").write(text)
     return 0
 
 
