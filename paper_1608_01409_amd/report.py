@@ -50,10 +50,13 @@ def time_gpu(fn, iters: int, warm: int = 3, warm_ms: float = 30.0) -> float:
     return e0.elapsed_time(e1) / iters
 
 
-def time_sparse(layer, w, xd, iters, plan=None):
+def time_sparse(layer, w, xd, iters, plan=None, tune=0):
+    """tune > 0: the library times that many of its best-ranked tilings first and keeps the fastest (sconv_tune)."""
     h = B.sconv_create_csr(layer, w, plan)
     info = B.sconv_csr_info(h)
     out = torch.empty((xd.shape[0], layer.K, info["OH"], info["OW"]), dtype=torch.float32, device="cuda")
+    if tune > 0 and plan is None:
+        B.sconv_tune(h, xd, out, max_plans=tune)
     ms = time_gpu(lambda: B.sconv_forward(h, xd, out), iters)
     return ms, B.sconv_csr_info(h), h   # the tiling is settled by the first forward call
 
@@ -91,13 +94,27 @@ def crossover(xs, t_sparse, t_dense):
     return None
 
 
+def knee(xs, ts):
+    """Density below which the measured time stops falling: where the line through the compute-bound points
+    (x >= 0.1, least squares of t against x) meets the floor (the time at the lowest density)."""
+    pts = [(x, t) for x, t in zip(xs, ts) if 0.09 <= x <= 0.55]
+    if len(pts) < 2:
+        return None, None, None
+    mx, mt = sum(p[0] for p in pts) / len(pts), sum(p[1] for p in pts) / len(pts)
+    slope = sum((p[0] - mx) * (p[1] - mt) for p in pts) / sum((p[0] - mx) ** 2 for p in pts)
+    icpt = mt - slope * mx
+    floor = ts[0]
+    return (floor - icpt) / slope if slope > 0 else None, icpt, slope
+
+
 def emit(row):
     print(json.dumps(row), flush=True)
 
 
-def report_sweep(iters):
-    print("# density sweep, AlexNet conv2-5, batch 256 (configuration 3)")
-    print(f"{'layer':6s} {'x':>5s} {'nnz':>8s} {'t_meas us':>10s} {'t_model us':>10s} {'TFLOP/s':>8s} "
+def report_sweep(iters, tune=16):
+    print(f"# density sweep, AlexNet conv2-5, batch 256 (configuration 3); tilings: the fastest of the library's {tune} "
+          "best-ranked per point (sconv_tune); t_model = Section 2.2's max(compute, bandwidth) + the machine's t_fixed")
+    print(f"{'layer':6s} {'x':>5s} {'nnz':>8s} {'t_meas us':>10s} {'t_model us':>10s} {'meas/model':>10s} {'TFLOP/s':>8s} "
           f"{'t_dense us':>10s} {'speedup':>8s} {'model spd':>9s}")
     for li, (name, N, _) in enumerate(wl.CONFIGS[1]):
         layer = wl.LAYERS[name]
@@ -110,7 +127,7 @@ def report_sweep(iters):
         pred1 = None
         for dens in wl.SWEEP_DENSITIES:
             _, w = wl.make_case(2, li, layer, 1, dens)
-            ms, info, h = time_sparse(layer, w, xd, iters)
+            ms, info, h = time_sparse(layer, w, xd, iters, tune=tune)
             pred = B.sconv_model_predict(layer, N, dens, h)
             pred1 = pred
             flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
@@ -120,7 +137,7 @@ def report_sweep(iters):
                        t_meas_us=ms * 1e3, t_model_us=pred["t_sparse"] * 1e6, tflops=flops / ms / 1e9,
                        t_dense_us=t_dense * 1e6, speedup=t_dense / (ms * 1e-3), model_speedup=pred["speedup"],
                        bandwidth_bound=bool(pred["bandwidth_bound"]), plan=info["plan"])
-            print(f"{name:6s} {dens:5.2f} {info['nnz']:8d} {ms*1e3:10.1f} {pred['t_sparse']*1e6:10.1f} "
+            print(f"{name:6s} {dens:5.2f} {info['nnz']:8d} {ms*1e3:10.1f} {pred['t_sparse']*1e6:10.1f} {ms*1e-3/pred['t_sparse']:10.2f} "
                   f"{flops/ms/1e9:8.2f} {t_dense*1e6:10.1f} {t_dense/(ms*1e-3):8.2f} {pred['speedup']:9.2f}")
             emit(row)
         xc = crossover(xs, ts, t_dense)
@@ -132,10 +149,18 @@ def report_sweep(iters):
         ratio = (xc / pm["x_lower"]) if xc else None
         # alpha as the paper measures it (Section 3.2): dense rate over the sparse kernel's rate at x = 1
         alpha_meas = (flops_dense / t_dense) / (flops_dense / ts[-1])
+        xk, icpt, slope = knee(xs, [t * 1e6 for t in ts])
+        pl = B.sconv_model_predict_lowered(layer, N, 0.1, None, m)
         print(f"{name}: measured crossover x = {xc}, model x_lower = {pm['x_lower']:.3f} (alpha {pm['alpha']:.2f} from the "
-              f"ceilings, {alpha_meas:.2f} from the x = 1 plateau; dense {m.dense_flops/1e12:.1f} TFLOP/s measured), "
-              f"model x_upper = {pm['x_upper']:.4f}, ratio {ratio}")
+              f"ceilings with lane_efficiency CALIBRATED to the x = 1 plateau, as the paper takes alpha from its measured plateau; "
+              f"{alpha_meas:.2f} from this run's plateau; dense {m.dense_flops/1e12:.1f} TFLOP/s measured), ratio {ratio}")
+        print(f"{name}: upper bound of useful sparsity: model x_upper = {pm['x_upper']:.4f}; measured knee x = {xk if xk is None else round(xk, 4)} "
+              f"(floor {ts[0]*1e6:.1f} us at x = {xs[0]:.3f}; compute-bound line {icpt:.1f} us + {slope:.0f} us * x), "
+              f"ratio {None if not xk else round(xk / pm['x_upper'], 2)}; density at which the line's compute part alone equals the floor "
+              f"(the section's own definition: compute time = bandwidth time) {ts[0]*1e6/slope:.4f}, ratio {ts[0]*1e6/slope/pm['x_upper']:.2f}; "
+              f"on lowered tensors the model's x_upper would be {pl['x_upper']:.4f}")
         emit(dict(report="crossover", layer=name, measured=xc, model_x_lower=pm["x_lower"], model_x_upper=pm["x_upper"],
+                  measured_knee=xk, fixed_us=icpt, us_per_unit_density=slope, lowered_x_upper=pl["x_upper"],
                   alpha=pm["alpha"], alpha_from_plateau=alpha_meas, dense_tflops=m.dense_flops / 1e12, ratio=ratio,
                   t_dense_conv_us=t_conv * 1e6, t_dense_gemm_us=t_gemm * 1e6))
 
@@ -164,17 +189,24 @@ def report_latency():
     med = float(np.median(ts))
     info = B.sconv_csr_info(h)
     flops = 2.0 * info["nnz"] * info["OH"] * info["OW"] * N
-    print(f"{name}: N {N} nnz {info['nnz']}: median {med*1e3:.1f} us (min {min(ts)*1e3:.1f}), {flops/med/1e6:.1f} GFLOP/s, "
-          f"plan {info['plan']}")
+    # the same launches back to back between one pair of events: what a stream of requests sees, without the
+    # 6-10 us that an event pair around a single launch adds (the wait for an idle queue to pick the launch up)
+    b2b = time_gpu(lambda: B.sconv_forward(h, xd, out), 200)
+    B.sconv_tune(h, xd, out, 24)
+    tuned = time_gpu(lambda: B.sconv_forward(h, xd, out), 200)
+    print(f"{name}: N {N} nnz {info['nnz']}: one launch between two events, median of 200: {med*1e3:.1f} us (min {min(ts)*1e3:.1f}), "
+          f"{flops/med/1e6:.1f} GFLOP/s; 200 launches back to back: {b2b*1e3:.1f} us each; the same with the tiling tuned "
+          f"(sconv_tune, 24 candidates): {tuned*1e3:.1f} us; plan {info['plan']} -> {B.sconv_csr_info(h)['plan']}")
     emit(dict(report="latency", layer=name, N=N, nnz=info["nnz"], median_us=med * 1e3, min_us=min(ts) * 1e3,
-              gflops=flops / med / 1e6, plan=info["plan"]))
+              back_to_back_us=b2b * 1e3, tuned_back_to_back_us=tuned * 1e3, gflops=flops / med / 1e6, plan=info["plan"]))
 
 
 def report_skewed(iters):
-    print("# skewed per-row densities, 20% empty rows, clustered columns, batch 256 (configuration 4)")
-    for li, name in enumerate(("conv3", "conv4")):
+    print("# skewed per-row densities, 20% empty rows, batch 256 (configuration 4); nonzeros clustered into active input "
+          "channels, or into one run of kernel positions per active channel")
+    for li, name, cluster in ((0, "conv3", "channels"), (1, "conv4", "channels"), (0, "conv3", "positions"), (1, "conv4", "positions")):
         layer = wl.LAYERS[name]
-        x, w = wl.make_case(3, li, layer, 256, 0.10, skewed=True)
+        x, w = wl.make_case(3, li, layer, 256, 0.10, skewed=True, cluster=cluster)
         xd = torch.from_numpy(x).cuda()
         nnz_row = (w.reshape(layer.K, -1) != 0).sum(1)
         ms, info, _ = time_sparse(layer, w, xd, iters)
@@ -184,10 +216,10 @@ def report_skewed(iters):
         _, wu = wl.make_case(3, li + 2, layer, 1, dens)
         msu, infou, _ = time_sparse(layer, wu, xd, iters)
         flu = 2.0 * infou["nnz"] * infou["OH"] * infou["OW"] * 256
-        row = dict(report="skewed", layer=name, nnz=info["nnz"], empty_rows=int((nnz_row == 0).sum()),
+        row = dict(report="skewed", layer=name, cluster=cluster, nnz=info["nnz"], empty_rows=int((nnz_row == 0).sum()),
                    max_row=int(nnz_row.max()), mean_row=float(nnz_row.mean()), t_us=ms * 1e3, tflops=flops / ms / 1e9,
                    uniform_t_us=msu * 1e3, uniform_tflops=flu / msu / 1e9, plan=info["plan"])
-        print(f"{name}: nnz {info['nnz']} rows empty {row['empty_rows']} max/mean {row['max_row']}/{row['mean_row']:.0f}: "
+        print(f"{name} ({cluster}): nnz {info['nnz']} rows empty {row['empty_rows']} max/mean {row['max_row']}/{row['mean_row']:.0f}: "
               f"{ms*1e3:.1f} us {row['tflops']:.2f} TFLOP/s; uniform mask of the same density: {msu*1e3:.1f} us "
               f"{row['uniform_tflops']:.2f} TFLOP/s")
         emit(row)
