@@ -78,10 +78,13 @@ SIGNAL_AFTER = 2
 
 # kernel-argument offsets the asm reads (checked by static_asserts next to the struct)
 OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
+OFF_PHASE = 264                                # blocks per phase, stride, source row bytes, bytes of one phase's channels: set below
 
 OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase", "slab0", "slabstep", "nslab",
        "lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff", "outp_hi", "nch", "nblk", "bias", "flags", "nwv"]
-IO_OPS = ["ctr"]               # in/out: LDS byte address of the counter of the block the wave is in (flow only)
+# in/out: LDS byte address of the counter of the block the wave is in (flow only); blocks left to stage before the
+# channel walk passes into the next phase of a strided layer, and that phase's column (both idle for other layers)
+IO_OPS = ["ctr", "wrap", "px"]
 FLAG_RELU = 0                  # bit of the flags operand
 OP = {n: f"%[{n}]" for n in OPS + IO_OPS}
 
@@ -182,6 +185,32 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
         emit(f"s_mul_i32 s{STMP}, s{SNCH}, s{SHW4}")
         emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{STMP}")
         emit(f"s_sub_u32 s{SREM}, s{SREM}, s{SNCH}")
+        # Strided layers staged straight from the caller's input: the virtual channels run phase by phase, and the
+        # blocks of a phase are that phase's real channels, a regular walk.  Past a phase's last block the walk
+        # returns to the group's first channel, one element further along the row (next column phase) or, past
+        # the last column phase, one row further and back to column phase 0.  Other layers never get here.
+        nowrap, nextrow, wrapped = label("nowrap"), label("nextrow"), label("wrapped")
+        emit(f"s_sub_u32 {OP['wrap']}, {OP['wrap']}, 1")
+        emit(f"s_cmp_lg_u32 {OP['wrap']}, 0")
+        emit(f"s_cbranch_scc1 {nowrap}")
+        emit(f"s_load_dwordx2 vcc, {OP['kern']}, {hex(OFF_PHASE)}")               # blocks per phase, stride
+        emit(f"s_load_dwordx2 s[{SNCH}:{STGT}], {OP['kern']}, {hex(OFF_PHASE + 8)}")   # row bytes, bytes of a phase's channels
+        emit("s_waitcnt lgkmcnt(0)")
+        emit(f"s_mov_b32 {OP['wrap']}, vcc_lo")
+        emit(f"s_sub_u32 s{SSOFF}, s{SSOFF}, s{STGT}")
+        emit(f"s_add_u32 {OP['px']}, {OP['px']}, 1")
+        emit(f"s_cmp_eq_u32 {OP['px']}, vcc_hi")
+        emit(f"s_cbranch_scc1 {nextrow}")
+        emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, 4")
+        emit(f"s_branch {wrapped}")
+        emit(f"{nextrow}:")
+        emit(f"s_mov_b32 {OP['px']}, 0")
+        emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{SNCH}")
+        emit("s_lshl_b32 vcc_hi, vcc_hi, 2")
+        emit(f"s_sub_u32 s{SSOFF}, s{SSOFF}, vcc_hi")
+        emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, 4")
+        emit(f"{wrapped}:")
+        emit(f"{nowrap}:")
 
     def body(A, B, N, n=CH, check=False):
         """One chunk: multiply the first n entries of A (8, or 4 for the half chunk that may open a segment);
@@ -481,7 +510,7 @@ struct Lds2Asm<{T}, {R}, {step}, {"true" if flow else "false"}> {{
                                                unsigned lim, unsigned ldsbase, unsigned slab0, unsigned slabstep,
                                                unsigned nslab, unsigned lane_byte, unsigned voff0, unsigned voff1,
                                                unsigned voff2, unsigned voff3, unsigned tbloff, unsigned nch, unsigned nblk,
-                                               unsigned long long bias, unsigned flags, unsigned nwv, unsigned ctr)
+                                               unsigned long long bias, unsigned flags, unsigned nwv, unsigned ctr, unsigned wrap, unsigned px)
     {{
         asm volatile(
 {chr(10).join(text)}
@@ -500,7 +529,7 @@ def generate() -> str:
         parts.append(gen_shape(*s))
         parts.append(gen_shape(*s, flow=True))
     parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r}, {st})" for t, r, _, _, st in SHAPES) + "\n")
-    parts.append(f"#define SCONV_LDS2_FLOW_BUFS {FLOW_BUFS}\n")
+    parts.append(f"#define SCONV_LDS2_FLOW_BUFS {FLOW_BUFS}\n#define SCONV_LDS2_OFF_PHASE {OFF_PHASE}\n")
     parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
                  f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")
     return "".join(parts)

@@ -59,6 +59,9 @@ struct sconv_csr {
     void *part_buf = nullptr; // partial results of launches that split the channels over workgroups
     size_t part_bytes = 0;
     const Canonical &kc() const { return phased ? kcanon : canon; }
+    // real channels per phase of a group when the phase images can be picked out of the caller's input while
+    // staging (a strided layer without padding), else 0
+    int phase_cg() const { return (phased && desc.pad == 0) ? desc.C / desc.groups : 0; }
     // fully connected use (sconv_fc_forward): the layer as a 1x1 convolution whose positions are the batch
     int fc_n = 0;            // batch size the arrays below were packed for
     int fc_tiles = 0;        // the batch is cut into this many tiles of fc_n / fc_tiles images
@@ -144,7 +147,7 @@ static int plan_lds(sconv_csr *h, int n, bool resident_only = false)
     auto known = h->plan_of_n.find(n);
     const bool fresh = known == h->plan_of_n.end();
     if (fresh && resident_only) return SCONV_ERR_PLAN; // never planned for this batch size
-    rc = make_lds_tiling(d, fresh ? h->requested : known->second, n, avg, t); // a known tiling has every field: no search
+    rc = make_lds_tiling(d, fresh ? h->requested : known->second, n, avg, t, h->phase_cg()); // a known tiling has every field: no search
     if (rc) return rc;
     auto remember = [&]() {
         if (!fresh) return;
@@ -458,7 +461,9 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
     // the per-row-stream kernel's tiles of 4 images and more are no match for the direct kernel on 1-3 images
     if (use_lds && !h->flat && h->requested.kernel == 0 && N < 4 && h->lds.t.p.nt >= 4) use_lds = false;
     int rc;
-    if (use_lds && h->phased) {
+    // the flat-stream kernel stages an unpadded strided layer straight from `in` when its blocks hold whole phases
+    const bool stage_phases = use_lds && h->phased && h->flat && f_tiling(h).phase_cg > 0;
+    if (use_lds && h->phased && !stage_phases) {
         // re-order the input into phase images (scratch owned by the handle, grown on demand)
         const size_t need = (size_t)N * h->kdesc.C * h->kdesc.H * h->kdesc.W * sizeof(float);
         float *phase;
@@ -491,7 +496,16 @@ static int forward_impl(sconv_csr *h, const float *in, float *out, int32_t N, co
             (void)static_scratch(&base, &bytes, &ignored);
         }
         const LdsTiling &ft = f_tiling(h);
-        return run_flat(h, h->kdesc, ft, h->dev_lds, nchw_layout(h->kdesc, ft), in, out, N, out_rows, out_inner, ep, hip_stream, ws);
+        Lds2Layout lay = nchw_layout(h->kdesc, ft);
+        if (stage_phases) {
+            // the input side of the layout is the caller's tensor; the output side is the same for both forms
+            const int64_t HW = (int64_t)h->desc.H * h->desc.W;
+            lay.phase_stride = h->desc.stride;
+            lay.src_w = h->desc.W;
+            lay.in_img = h->desc.C * HW; lay.in_tile = 4 * lay.in_img; lay.in_ch = HW; lay.in_pos = 1;
+            lay.in_rec_fixed = 0; lay.in_rec_img = lay.in_img * 4; lay.in_rec_tile = 0;
+        }
+        return run_flat(h, h->kdesc, ft, h->dev_lds, lay, in, out, N, out_rows, out_inner, ep, hip_stream, ws);
     }
     if (use_lds) {
         if (!h->lds_uploaded) {
@@ -780,7 +794,7 @@ extern "C" int sconv_rank_plans(const sconv_csr *h, int32_t N, int32_t max_plans
     try {
         const double avg = h->kdesc.K ? (double)h->canon.val.size() / h->kdesc.K : 0.0;
         std::vector<LdsTiling> cands;
-        const int rc = rank_lds_tilings(h->kdesc, h->requested, N < 4 ? 4 : N, avg, clamp_plans(max_plans), cands);
+        const int rc = rank_lds_tilings(h->kdesc, h->requested, N < 4 ? 4 : N, avg, clamp_plans(max_plans), cands, h->phase_cg());
         if (rc) return rc;
         for (const LdsTiling &t : cands) plans[(*count)++] = t.p;
     } catch (const std::bad_alloc &) {
@@ -801,7 +815,7 @@ extern "C" int sconv_tune(sconv_csr *h, const float *in, float *out, int32_t N, 
     try {
         const double avg = h->kdesc.K ? (double)h->canon.val.size() / h->kdesc.K : 0.0;
         std::vector<LdsTiling> cands;
-        int rc = rank_lds_tilings(h->kdesc, h->requested, n_plan, avg, clamp_plans(max_plans), cands);
+        int rc = rank_lds_tilings(h->kdesc, h->requested, n_plan, avg, clamp_plans(max_plans), cands, h->phase_cg());
         if (rc) return rc;
         int best = -1;
         StashRoom room(h, cands.size());

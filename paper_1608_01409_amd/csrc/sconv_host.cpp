@@ -118,7 +118,7 @@ static int lds_pitch(const sconv_desc &d, int strip = 0)
     return pitch;
 }
 
-static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
+static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t, int phase_cg = 0)
 {
     const Geometry g = geometry(d);
     if (d.stride != 1) return SCONV_ERR_PLAN;
@@ -157,6 +157,9 @@ static int fill_tiling(const sconv_desc &d, const sconv_plan &p, LdsTiling &t)
     }
     if (p.cb > g.Cg) t.p.cb = g.Cg;
     t.nblk = ceil_div(g.Cg, t.p.cb);
+    // A strided layer without padding can be staged straight from the caller's input when no channel block
+    // straddles two phases (the virtual channels are ordered phase by phase, phase_cg real channels each)
+    t.phase_cg = (phase_cg > 0 && flat && phase_cg % t.p.cb == 0) ? phase_cg : 0;
     if (t.p.splits > t.nblk) return SCONV_ERR_PLAN;
     // every part takes ceil(nblk / splits) blocks; fewer parts if the last ones would be empty
     t.p.splits = ceil_div(t.nblk, ceil_div(t.nblk, t.p.splits));
@@ -299,13 +302,13 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
 }
 
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
-                              std::vector<std::pair<double, LdsTiling>> *all);
+                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg = 0);
 // whether the library, left to itself, considers the flow variant of the flat-stream kernel
 static const bool kFlowByDefault = true;
 
-int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out)
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg)
 {
-    return search_lds_tilings(d, req, N_hint, avg_row_nnz, out, nullptr);
+    return search_lds_tilings(d, req, N_hint, avg_row_nnz, out, nullptr, phase_cg);
 }
 
 static bool same_tiling(const sconv_plan &a, const sconv_plan &b)
@@ -315,11 +318,11 @@ static bool same_tiling(const sconv_plan &a, const sconv_plan &b)
 }
 
 int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
-                     std::vector<LdsTiling> &out)
+                     std::vector<LdsTiling> &out, int phase_cg)
 {
     std::vector<std::pair<double, LdsTiling>> all;
     LdsTiling best;
-    const int rc = search_lds_tilings(d, req, N_hint, avg_row_nnz, best, &all);
+    const int rc = search_lds_tilings(d, req, N_hint, avg_row_nnz, best, &all, phase_cg);
     if (rc) return rc;
     std::stable_sort(all.begin(), all.end(), [](const std::pair<double, LdsTiling> &a, const std::pair<double, LdsTiling> &b) {
         return a.first < b.first;
@@ -335,13 +338,13 @@ int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, dou
 }
 
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
-                              std::vector<std::pair<double, LdsTiling>> *all)
+                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg)
 {
     const Geometry g = geometry(d);
     if (d.stride != 1) return SCONV_ERR_PLAN;
     const bool full = req.nt && req.cb && req.waves && req.cg && req.rows_w && req.t;
     if (full) {
-        const int rc = fill_tiling(d, req, out);
+        const int rc = fill_tiling(d, req, out, phase_cg);
         if (!rc && all) all->emplace_back(0.0, out);
         return rc;
     }
@@ -390,6 +393,11 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                     if (cb < 1) continue;
                     // even out the blocks
                     if (!req.cb) cb = ceil_div(g.Cg, ceil_div(g.Cg, cb));
+                    // a strided layer staged straight from the input: blocks of whole phases' channels
+                    if (!req.cb && phase_cg > 0 && flat) {
+                        cb = std::min(cb, phase_cg);
+                        while (phase_cg % cb) --cb;
+                    }
                     // channel blocks of a tile shared by several workgroups, when there are too few tiles
                     static const int split_choices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
                     for (int sp : split_choices) {
@@ -397,7 +405,7 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                         const int splits = req.splits ? req.splits : sp;
                         sconv_plan p = {kind, nt, cb, waves, cg, rows_w, T, band, strip, splits};
                         LdsTiling t;
-                        if (fill_tiling(d, p, t) != SCONV_OK) continue;
+                        if (fill_tiling(d, p, t, phase_cg) != SCONV_OK) continue;
                         if (!req.splits && t.p.splits != sp) continue; // the same as a smaller choice
                         const double c = flat ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
                                                    : tiling_cost(d, t, N_hint, avg_row_nnz);
@@ -767,7 +775,7 @@ int phase_canonical(const sconv_desc &d, const Canonical &c, Canonical &vc)
             const int off = c.off[j];
             const int t = off % g.Wp, r = (off / g.Wp) % g.Hp, ca = off / (g.Wp * g.Hp);
             const int cl = ca - grp * g.Cg;
-            const int va = grp * gv.Cg + (cl * s + r % s) * s + t % s;
+            const int va = grp * gv.Cg + ((r % s) * s + t % s) * g.Cg + cl; // phase by phase, the group's channels inside
             rows[k].push_back({(va * gv.Hp + r / s) * gv.Wp + t / s, c.val[j]});
         }
     }
@@ -799,7 +807,7 @@ int unphase_canonical(const sconv_desc &d, const Canonical &vc, Canonical &out)
             const int off = vc.off[j];
             const int t2 = off % gv.Wp, r2 = (off / gv.Wp) % gv.Hp, va = off / (gv.Wp * gv.Hp);
             const int vl = va - grp * gv.Cg;
-            const int px = vl % s, py = (vl / s) % s, cl = vl / (s * s);
+            const int cl = vl % g.Cg, px = (vl / g.Cg) % s, py = vl / (g.Cg * s);
             const int r = r2 * s + py, t = t2 * s + px;
             if (r >= d.R || t >= d.S) return SCONV_ERR_CSR;
             rows[k].push_back({((grp * g.Cg + cl) * g.Hp + r) * g.Wp + t, vc.val[j]});

@@ -58,6 +58,8 @@ struct LdsTiling {
     int n_slabs;        // 64-float slabs per channel plane (staging granule)
     int n_bufs;         // LDS block buffers: 2 (double-buffered; 3 for the flow variant) unless the layer has fewer blocks
     int ctr_bytes_at;   // flow variant: byte offset in LDS of its per-block counters (nblk dwords), else 0
+    int phase_cg;       // > 0: stride-1 form of a strided, unpadded layer whose blocks hold whole phases' channels
+                        // (that many real channels per phase): staged straight from the caller's input
     int buf_stride_floats; // floats from one buffer to the next: block + zero page, multiple of 4
     int lds_bytes;      // dynamic LDS per workgroup
     unsigned zero_page; // byte offset, relative to a buffer, of its all-zero page (padding entries)
@@ -112,10 +114,12 @@ int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, cons
 
 // Fill in a tiling for the LDS kernel (fields of `req` that are 0 are chosen).  N_hint is the
 // batch size the choice is tuned for.  Returns SCONV_ERR_PLAN if the layer cannot use it.
-int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out);
+// phase_cg > 0: d is the stride-1 form of a strided layer without padding, with that many real channels per
+// phase; tilings whose blocks hold whole phases' channels can then be staged without the phase-image pass.
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg = 0);
 // The max_out distinct tilings the cost model ranks best, best first (out[0] is make_lds_tiling's choice).
 int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
-                     std::vector<LdsTiling> &out);
+                     std::vector<LdsTiling> &out, int phase_cg = 0);
 // p.kernel selects the shape list: 1 = per-row streams, 3 = flat streams (nt must be 4)
 bool lds_kernel_available(int vec, int t, int rows_w);
 
@@ -132,7 +136,7 @@ int unpack_direct(const sconv_desc &d, const PackedDirect &p, Canonical &out);
 // Strided layers on the LDS kernels.  With stride s the input rows that one filter row r touches are
 // y*s + r: split r = r'*s + py and they become rows y + r' of the "phase image" py (every s-th row of the
 // padded image, starting at py), and the same along x.  A strided layer is therefore a stride-1, pad-0 layer
-// over Cg*s*s virtual channels (c, py, px) of size Hq x Wq = (OH + R' - 1) x (OW + S' - 1) with an R' x S'
+// over Cg*s*s virtual channels (py, px, c: phase by phase) of size Hq x Wq = (OH + R' - 1) x (OW + S' - 1) with an R' x S'
 // filter, R' = ceil(R/s): no input element is duplicated, only re-ordered (Section 2.1 allows any layout
 // function f that is additive in the output position).  phase_desc gives that layer, phase_canonical its
 // CSR; unphase_canonical maps offsets of the virtual layer back to the real one.
@@ -159,6 +163,10 @@ struct Epilogue {
 // of tile m, row k, band b, position q inside the band): m*out_tile + b*out_band + k*out_row + i*out_img +
 // q*out_pos.  nchw_layout() gives the convolution's [N][C][H][W] -> [N][K][OH][OW].
 struct Lds2Layout {
+    // phase_stride > 1: the input is the strided layer's own [N][C][H][src_w] tensor and the kernel picks the
+    // phase images out of it while staging (cell (Y, X) of phase (py, px) is input (Y*s + py, X*s + px));
+    // the tiling's phase_cg real channels make up one phase of a group
+    int phase_stride = 1, src_w = 0;
     int64_t in_tile, in_img, in_ch, in_pos;
     int64_t in_rec_fixed, in_rec_img, in_rec_tile; // bytes tile m with n valid images may read: fixed + n * img - m * tile
     int64_t out_tile, out_band, out_row, out_img, out_pos;

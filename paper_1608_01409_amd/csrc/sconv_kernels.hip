@@ -255,6 +255,10 @@ struct Lds2Args {
     const float *bias;       // [K] added to every output of row k, or null
     int relu;                // outputs below zero become zero
     int ctr_bytes_at;        // flow: LDS byte offset of the per-block landing counters (one dword per block)
+    // strided layers staged straight from the caller's input (phase_stride > 1), else {huge, 1, 0, 0}: read by the asm
+    int blocks_per_phase, phase_stride, src_row_bytes, phase_span_bytes; // phase_span = the group's channels of one phase
+    int phase_cg;            // real channels per phase of a group
+    FastDiv d_pcg, d_pstride;
     FastDiv d_units, d_splits, d_bands, d_nkt, d_cg, d_wl, d_strip; // the divisors of the index arithmetic below
 };
 
@@ -266,6 +270,8 @@ static_assert(offsetof(Lds2Args, pairs) == SCONV_LDS2_OFF_PAIRS, "asm reads pair
 static_assert(offsetof(Lds2Args, store_tbl) == SCONV_LDS2_OFF_TBL, "asm reads store_tbl here");
 static_assert(offsetof(Lds2Args, cb) == SCONV_LDS2_OFF_CONSTS, "asm reads eight constants from here");
 static_assert(offsetof(Lds2Args, img_stride_bytes) == SCONV_LDS2_OFF_CONSTS + 28, "layout of the constants");
+static_assert(offsetof(Lds2Args, blocks_per_phase) == SCONV_LDS2_OFF_PHASE, "asm reads the four phase constants from here");
+static_assert(offsetof(Lds2Args, phase_span_bytes) == SCONV_LDS2_OFF_PHASE + 12, "layout of the phase constants");
 
 constexpr unsigned kSkipLane = 0xFFFFFFFFu; // lane past the end of a plane: writes nothing
 constexpr unsigned kZeroLane = 0x80000000u; // padding cell: beyond num_records, the load returns 0
@@ -319,6 +325,16 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         const int f = (wave + j * n_waves) * 64 + lane;
         const int cell = f >> 2, img = f & 3;
         const int Y = fdiv(cell, a.d_wl), X = cell - Y * a.Wl;
+        if (a.phase_stride > 1) {
+            // cell (Y, X) of a phase image is element (Y*s, X*s) of the caller's plane, shifted by the phase,
+            // which the scalar offset of the channel carries.  There is no padding (the host sends only unpadded
+            // layers this way), and every cell a stored weight reads for a real output lies inside the image:
+            // cells beyond it hold whatever follows in memory (zeros past the tensor's end, by the range check)
+            // and are read only by lanes whose results are dropped.
+            voff[j] = f >= a.plane_floats ? kSkipLane
+                                          : (unsigned)(img * a.in_img + ((y0 + Y) * a.phase_stride * (a.src_row_bytes >> 2) + X * a.phase_stride)) * 4u;
+            continue;
+        }
         const int iy = y0 + Y - a.pad, ix = X - a.pad;
         const bool inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
         voff[j] = f >= a.plane_floats ? kSkipLane
@@ -376,19 +392,28 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         cell0 = y * a.Wl + bx;
         if (by >= a.strip_rows || y >= a.band) cell0 &= 15;
     }
+    // scalar offset of the first channel this workgroup stages, and where it stands in its phase
+    unsigned soff0 = (unsigned)((g * a.Cg + ch0) * a.HW4), blocks_to_wrap = 0x7fffffffu, px0 = 0;
+    if (a.phase_stride > 1) {
+        const int ph = fdiv(ch0, a.d_pcg), c0 = ch0 - ph * a.phase_cg, py = fdiv(ph, a.d_pstride), px = ph - py * a.phase_stride;
+        soff0 = (unsigned)(g * a.phase_span_bytes + c0 * a.HW4 + py * a.src_row_bytes + px * 4);
+        blocks_to_wrap = (unsigned)((a.phase_cg - c0) / a.cb);
+        px0 = (unsigned)px;
+    }
     const unsigned long long bias = (unsigned long long)a.bias;
     const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane(a.relu ? 1 : 0);
     Lds2Asm<T, R, STEP, FLOW>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
                        a.seg + ((size_t)wslot * a.nblk + blk0) * 2,
                        a.row_of + (size_t)wslot * R,
                        __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
-                       (unsigned)__builtin_amdgcn_readfirstlane((g * a.Cg + ch0) * a.HW4), (unsigned)nimg, lim,
+                       (unsigned)__builtin_amdgcn_readfirstlane(soff0), (unsigned)nimg, lim,
                        __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)(wave * 256), (unsigned)(n_waves * 256),
                        (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)(cell0 * 16), voff[0],
                        voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4),
                        (unsigned)__builtin_amdgcn_readfirstlane(nch_here), (unsigned)__builtin_amdgcn_readfirstlane(nblk_here),
                        bias, flags, (unsigned)__builtin_amdgcn_readfirstlane(n_waves),
-                       (unsigned)__builtin_amdgcn_readfirstlane(ldsbase + (unsigned)a.ctr_bytes_at));
+                       (unsigned)__builtin_amdgcn_readfirstlane(ldsbase + (unsigned)a.ctr_bytes_at),
+                       (unsigned)__builtin_amdgcn_readfirstlane(blocks_to_wrap), (unsigned)__builtin_amdgcn_readfirstlane(px0));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -769,6 +794,20 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     a.strip = t.p.strip; a.strip_rows = t.strip_rows;
     a.n_bufs = t.n_bufs;
     a.ctr_bytes_at = t.ctr_bytes_at;
+    a.blocks_per_phase = 0x7fffffff; a.phase_stride = 1; a.src_row_bytes = 0; a.phase_span_bytes = 0; a.phase_cg = 0;
+    a.d_pcg = make_fastdiv(1, 1); a.d_pstride = make_fastdiv(1, 1);
+    if (lay.phase_stride > 1) {
+        // d is the stride-1 form of the layer; the caller's tensor has C / s^2 channels of lay.in_ch floats
+        if (t.phase_cg <= 0 || t.phase_cg % t.p.cb || d.pad != 0 || lay.in_pos != 1 || lay.src_w <= 0) return SCONV_ERR_PLAN;
+        if (g.Cg != t.phase_cg * lay.phase_stride * lay.phase_stride) return SCONV_ERR_PLAN;
+        a.phase_stride = lay.phase_stride;
+        a.blocks_per_phase = t.phase_cg / t.p.cb;
+        a.src_row_bytes = lay.src_w * 4;
+        a.phase_span_bytes = (int)(t.phase_cg * lay.in_ch * 4);
+        a.phase_cg = t.phase_cg;
+        a.d_pcg = make_fastdiv(t.phase_cg, g.Cg);
+        a.d_pstride = make_fastdiv(lay.phase_stride, lay.phase_stride * lay.phase_stride);
+    }
     // with several parts the kernel stores partial sums into the workspace `out` points to, part after part,
     // and the reduction that follows applies the epilogue
     a.split_stride = a.splits > 1 ? split_stride : 0;
@@ -820,12 +859,12 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
     return SCONV_ERR_PLAN;
 }
 
-// Phase images of a strided layer: q[n][(c*s + py)*s + px][Y][X] = in_pad[n][c][Y*s + py][X*s + px], the
+// Phase images of a strided layer: q[n][virtual channel of (c, py, px)][Y][X] = in_pad[n][c][Y*s + py][X*s + px], the
 // zero padding written out.  One thread per element of q; consecutive threads write consecutive X.
 struct PhaseArgs {
     const float *in;
     float *q;
-    int C, H, W, s, pad, Hq, Wq;
+    int C, Cg, H, W, s, pad, Hq, Wq;
     long long total;
 };
 
@@ -839,7 +878,9 @@ __global__ void __launch_bounds__(256) sconv_phase_kernel(const PhaseArgs a)
     rest /= a.Hq;
     const int cv = (int)(rest % (a.C * a.s * a.s));
     const long long n = rest / (a.C * a.s * a.s);
-    const int px = cv % a.s, py = (cv / a.s) % a.s, c = cv / (a.s * a.s);
+    // virtual channels run group by group, inside a group phase by phase, inside a phase over the group's channels
+    const int per_group = a.Cg * a.s * a.s, grp = cv / per_group, rem = cv - grp * per_group;
+    const int ph = rem / a.Cg, c = grp * a.Cg + rem - ph * a.Cg, py = ph / a.s, px = ph - py * a.s;
     const int iy = Y * a.s + py - a.pad, ix = X * a.s + px - a.pad;
     float v = 0.f;
     if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) v = a.in[((n * a.C + c) * a.H + iy) * a.W + ix];
@@ -851,7 +892,7 @@ int launch_phase(const sconv_desc &d, const sconv_desc &v, const float *in, floa
     PhaseArgs a;
     a.in = in;
     a.q = q;
-    a.C = d.C; a.H = d.H; a.W = d.W; a.s = d.stride; a.pad = d.pad; a.Hq = v.H; a.Wq = v.W;
+    a.C = d.C; a.Cg = d.C / d.groups; a.H = d.H; a.W = d.W; a.s = d.stride; a.pad = d.pad; a.Hq = v.H; a.Wq = v.W;
     a.total = (long long)N * v.C * v.H * v.W;
     const long long gx = (a.total + 255) / 256;
     if (gx > 0x7fffffff) return SCONV_ERR_RANGE;

@@ -327,3 +327,42 @@ def test_channel_splits_without_epilogue(oracle, splits, kernel):
     x, w = rand_case(BIG, 6, 0.2, seed=73)
     _, info = check(BIG, w, x, oracle, plan, what="splits")
     assert info["plan"]["splits"] == splits
+
+
+STRIDED = wl.small_layer("strided", C=8, H=23, W=21, K=12, R=5, S=3, stride=2, pad=0, groups=2)
+STRIDED_PLANS = [
+    dict(nt=4, cb=2, waves=4, cg=1, rows_w=8, t=2),             # two blocks per phase
+    dict(nt=4, cb=4, waves=4, cg=1, rows_w=8, t=2),             # one block per phase
+    dict(nt=4, cb=1, waves=8, cg=1, rows_w=8, t=2),             # four blocks per phase
+    dict(nt=4, cb=3, waves=4, cg=1, rows_w=8, t=2),             # blocks straddle phases: the phase-image pass runs instead
+    dict(nt=4, cb=2, waves=4, cg=1, rows_w=8, t=2, splits=2),   # channel parts that start in the middle of the phases
+    dict(nt=4, cb=1, waves=4, cg=1, rows_w=12, t=2, splits=3),
+    dict(nt=4, cb=2, waves=4, cg=1, rows_w=16, t=1, band=4),    # bands of output rows
+]
+
+
+@pytest.mark.parametrize("kernel", [3, 4])
+@pytest.mark.parametrize("plan", STRIDED_PLANS, ids=[str(i) for i in range(len(STRIDED_PLANS))])
+def test_strided_unpadded_layer_staged_from_the_input(oracle, plan, kernel):
+    """A strided layer without padding needs no phase-image pass: the kernel picks the phases out of the
+    caller's tensor while staging, provided no channel block straddles two phases.  Two groups, 5 x 3 filter,
+    stride 2; ragged batch; one row without nonzeros."""
+    x, w = rand_case(STRIDED, 9, 0.3, seed=83)
+    w[4] = 0
+    _, info = check(STRIDED, w, x, oracle, dict(plan, kernel=kernel), what="strided-direct")
+    assert info["plan"]["cb"] == plan["cb"] and info["plan"]["kernel"] == kernel
+
+
+def test_strided_unpadded_layer_inputs_with_non_finite_values(oracle):
+    """Cells of a phase image that lie beyond the input are filled with whatever follows in memory; they must
+    reach no real output, whatever they hold: here the neighbouring channels and images hold Inf and NaN."""
+    layer = wl.small_layer("strided2", C=3, H=19, W=19, K=8, R=7, S=7, stride=4, pad=0, groups=1)
+    x, w = rand_case(layer, 6, 0.4, seed=85)
+    x[:, :, 0, 0] = np.inf
+    x[:, 1, -1, -1] = np.nan
+    h = B.sconv_create_csr(layer, w)
+    got = B.sconv_forward(h, torch.from_numpy(x).cuda()).cpu().numpy()
+    ref, ab, _ = oracle.sparse_conv(layer, w, x)
+    fin = np.isfinite(ref)
+    assert np.array_equal(np.isfinite(got), fin)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= TOL * ab[fin])

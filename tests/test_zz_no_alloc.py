@@ -104,18 +104,27 @@ def test_refusals():
     assert L.sconv_forward_noalloc(None, None, None, 8, None) == B.ERR["NULL"]
     assert L.sconv_forward_noalloc(h.handle, None, C.c_void_p(out.data_ptr()), 8, None) == B.ERR["NULL"]
     assert L.sconv_forward_noalloc(h.handle, C.c_void_p(xd.data_ptr()), C.c_void_p(out.data_ptr()), 0, None) == B.ERR["BATCH"]
-    # more scratch than the static array holds: AlexNet conv1 at batch 128 wants 80 MB of phase images
-    conv1 = wl.LAYERS["conv1"]
-    x1, w1 = rand_case(conv1, 128, 0.3, seed=94)
-    h1 = B.sconv_create_csr(conv1, w1)
+    # more scratch than the static array holds: a padded stride-2 layer at batch 96 wants 83 MB of phase images
+    big = wl.small_layer("strided-padded", C=64, H=56, W=56, K=64, R=3, S=3, stride=2, pad=1, groups=1)
+    x1, w1 = rand_case(big, 96, 0.1, seed=94)
+    h1 = B.sconv_create_csr(big, w1)
     x1d = torch.from_numpy(x1).cuda()
     o1 = B.sconv_forward(h1, x1d)
-    need = 128 * conv1.C * 16 * 57 * 57 * 4
+    need = 96 * big.C * 4 * 29 * 29 * 4
     assert need > B.NOALLOC_SCRATCH_BYTES
     o2 = torch.zeros_like(o1)
     assert raw_noalloc(h1, x1d, o2) == B.ERR["CAPACITY"]
-    assert raw_noalloc(h1, x1d[:64].contiguous(), o2[:64]) == B.ERR["PLAN"]   # would fit, but batch 64 was never prepared
-    B.sconv_forward(h1, x1d[:64].contiguous(), o2[:64])
-    o3 = torch.full_like(o2[:64], float("nan"))
-    assert raw_noalloc(h1, x1d[:64].contiguous(), o3) == 0
-    assert torch.equal(o3, o2[:64])
+    assert raw_noalloc(h1, x1d[:24].contiguous(), o2[:24]) == B.ERR["PLAN"]   # would fit, but batch 24 was never prepared
+    B.sconv_forward(h1, x1d[:24].contiguous(), o2[:24])
+    o3 = torch.full_like(o2[:24], float("nan"))
+    assert raw_noalloc(h1, x1d[:24].contiguous(), o3) == 0
+    assert torch.equal(o3, o2[:24])
+    # an unpadded strided layer needs no scratch at all: the kernel picks the phases out of the input
+    conv1 = wl.LAYERS["conv1"]
+    xc, wc = rand_case(conv1, 128, 0.3, seed=95)
+    hc = B.sconv_create_csr(conv1, wc)
+    xcd = torch.from_numpy(xc).cuda()
+    oc = B.sconv_forward(hc, xcd)
+    oc2 = torch.full_like(oc, float("nan"))
+    assert raw_noalloc(hc, xcd, oc2) == 0
+    assert torch.equal(oc2, oc)
