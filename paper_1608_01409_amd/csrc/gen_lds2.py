@@ -50,7 +50,7 @@ import sys
 # consecutive cells of the plane (chunk t = the next 64 cells), w when they span a block of 64/w rows by w
 # columns (chunk t = the same rows, the next w columns).  The step is an immediate of the read instruction.
 SHAPES = [
-    (1, 16, 4, True, 64), (2, 8, 4, True, 64), (2, 12, 1, True, 64), (3, 4, 2, True, 64), (3, 6, 2, True, 64),
+    (1, 8, 4, True, 64), (1, 12, 4, True, 64), (1, 16, 4, True, 64), (2, 8, 4, True, 64), (2, 12, 1, True, 64), (3, 4, 2, True, 64), (3, 6, 2, True, 64),
     (3, 8, 1, True, 64), (4, 4, 2, True, 64), (4, 5, 1, True, 64), (5, 3, 2, True, 64), (5, 4, 1, True, 64),
     (6, 3, 1, True, 64), (7, 2, 2, False, 64), (7, 3, 1, False, 64), (13, 1, 1, False, 64),
     (3, 4, 2, True, 9), (3, 6, 2, True, 9), (3, 8, 1, True, 9),            # 27 columns in 3 strips of 9
@@ -75,6 +75,10 @@ MAX_VGPR = 128
 FLOW_LOOK = 1
 FLOW_BUFS = FLOW_LOOK + 2
 SIGNAL_AFTER = 2
+# L2 warming of the stream: each lane of one load touches one line of this many bytes, 64 lines from the point the
+# scalar loads have reached.  The host pads the stream by WARM_BYTES so that the last wave slot's loads stay inside.
+WARM_LINE_SHIFT = 6
+WARM_BYTES = 64 << WARM_LINE_SHIFT
 
 # kernel-argument offsets the asm reads (checked by static_asserts next to the struct)
 OFF_PAIRS, OFF_TBL, OFF_CONSTS = 16, 40, 48   # consts: cb nblk Cg plane stride HW4 OHW4 img_stride
@@ -85,7 +89,8 @@ OPS = ["kern", "rsrc", "segp", "rowp", "outp", "soff0", "nimg", "lim", "ldsbase"
 # in/out: LDS byte address of the counter of the block the wave is in (flow only); blocks left to stage before the
 # channel walk passes into the next phase of a strided layer, and that phase's column (both idle for other layers)
 IO_OPS = ["ctr", "wrap", "px"]
-FLAG_RELU = 0                  # bit of the flags operand
+FLAG_RELU = 0                  # bits of the flags operand
+FLAG_WIDE = 1                  # stage whole cells (16 bytes a lane) instead of dwords
 OP = {n: f"%[{n}]" for n in OPS + IO_OPS}
 
 
@@ -102,7 +107,8 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
     VA0 = RING0 + ring_regs
     VLB = VA0 + n_va        # lane base for the current buffer
     VS0, VS1 = VLB + 1, VLB + 2     # scratch of the counter operations (flow)
-    assert VS1 + 1 <= MAX_VGPR
+    VWARM = VLB + 3                 # destination of the loads that warm L2 with the stream: never read
+    assert VWARM + 1 <= MAX_VGPR
 
     def q(slot, t, e=None):
         b = RING0 + (slot * T + t) * 4
@@ -148,9 +154,21 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
         emit(f"s_branch {again}")
         emit(f"{go}:")
 
-    def stage(tgt):
-        """Issue the DMA loads of the next block (channels SSOFF.. , min(SCB, SREM) of them) into LDS at tgt."""
-        emit(f"s_min_u32 s{SNCH}, s{SCB}, s{SREM}")
+    def warm():
+        """Pull the next WARM_BYTES of this wave's stream into L2: one vector load, a line per lane, result
+        unused.  The stream reaches the chunk buffers through scalar loads that are waited for one chunk after
+        they are issued; a workgroup whose stream nobody has read before (a layer with a single image tile: every
+        fully connected layer) would otherwise pay a trip to HBM per chunk."""
+        emit(f"v_mbcnt_lo_u32_b32 v{VS0}, -1, 0")
+        emit(f"v_mbcnt_hi_u32_b32 v{VS0}, -1, v{VS0}")
+        emit(f"v_lshlrev_b32 v{VS0}, {WARM_LINE_SHIFT}, v{VS0}")
+        emit(f"v_add_u32 v{VS0}, s{SOFF}, v{VS0}")
+        emit(f"global_load_dword v{VWARM}, v{VS0}, s[{SPTR}:{SPTR + 1}]")
+
+    def stage_loads(tgt, load):
+        """The loads of one block for the (at most four) slabs of this wave: per slab one instruction per channel,
+        each lane moving a dword (16 cells x 4 images per instruction) or, where the four images of a cell are
+        adjacent in memory, a whole cell (64 cells per instruction)."""
         emit(f"s_add_u32 s{STMP}, s{tgt}, {OP['slab0']}")
         end = label("stend")
         for j in range(4):
@@ -168,7 +186,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
             emit(f"s_cbranch_scc1 {tail}")
             emit(f"{lp}:")
             for _ in range(2):
-                emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
+                emit(f"{load} {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
                 emit(f"s_add_u32 m0, m0, s{SPLANE}")
                 emit(f"s_add_u32 s{SS}, s{SS}, s{SHW4}")
             emit("s_sub_u32 vcc_lo, vcc_lo, 1")
@@ -177,10 +195,22 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
             emit(f"{tail}:")
             emit(f"s_bitcmp1_b32 s{SNCH}, 0")
             emit(f"s_cbranch_scc0 {nxt}")
-            emit(f"buffer_load_dword {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
+            emit(f"{load} {OP['voff%d' % j]}, {OP['rsrc']}, s{SS} offen lds")
             emit(f"{nxt}:")
             emit(f"s_add_u32 s{STMP}, s{STMP}, {OP['slabstep']}")
         emit(f"{end}:")
+
+    def stage(tgt):
+        """Issue the DMA loads of the next block (channels SSOFF.. , min(SCB, SREM) of them) into LDS at tgt."""
+        emit(f"s_min_u32 s{SNCH}, s{SCB}, s{SREM}")
+        wide, staged = label("stwide"), label("staged")
+        emit(f"s_bitcmp1_b32 {OP['flags']}, {FLAG_WIDE}")
+        emit(f"s_cbranch_scc1 {wide}")
+        stage_loads(tgt, "buffer_load_dword")
+        emit(f"s_branch {staged}")
+        emit(f"{wide}:")
+        stage_loads(tgt, "buffer_load_dwordx4")
+        emit(f"{staged}:")
         emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
         emit(f"s_mul_i32 s{STMP}, s{SNCH}, s{SHW4}")
         emit(f"s_add_u32 s{SSOFF}, s{SSOFF}, s{STMP}")
@@ -292,6 +322,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
     emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
     emit(f"s_load_dwordx16 s[{SB}:{SB + W - 1}], s[{SPTR}:{SPTR + 1}], s{SOFF}")
     emit(f"s_add_u32 s{SOFF}, s{SOFF}, {hex(4 * W)}")
+    warm()
     if flow:
         if FLOW_LOOK == 2:
             one = label("oneblock")
@@ -347,6 +378,7 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
         emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
         emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
         stage(STGT)
+    warm()                                                 # youngest load of the block: the staging loads are not held up
     emit(f"{nostage}:")
     emit(f"s_cmp_eq_u32 s{SCNT}, s{SOFF}")
     emit(f"s_cbranch_scc1 {segdone}")
@@ -529,7 +561,8 @@ def generate() -> str:
         parts.append(gen_shape(*s))
         parts.append(gen_shape(*s, flow=True))
     parts.append("\n#define SCONV_LDS2_SHAPES(X) " + " ".join(f"X({t}, {r}, {st})" for t, r, _, _, st in SHAPES) + "\n")
-    parts.append(f"#define SCONV_LDS2_FLOW_BUFS {FLOW_BUFS}\n#define SCONV_LDS2_OFF_PHASE {OFF_PHASE}\n")
+    parts.append(f"#define SCONV_LDS2_FLOW_BUFS {FLOW_BUFS}\n#define SCONV_LDS2_OFF_PHASE {OFF_PHASE}\n"
+                 f"#define SCONV_LDS2_WARM_BYTES {WARM_BYTES}\n")
     parts.append(f"#define SCONV_LDS2_OFF_PAIRS {OFF_PAIRS}\n#define SCONV_LDS2_OFF_TBL {OFF_TBL}\n"
                  f"#define SCONV_LDS2_OFF_CONSTS {OFF_CONSTS}\n")
     return "".join(parts)

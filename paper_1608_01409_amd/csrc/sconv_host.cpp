@@ -638,8 +638,8 @@ int pack_flat(const sconv_desc &d, const Canonical &c, const LdsTiling &t, Packe
         }
     }
     if (real != c.val.size()) return SCONV_ERR_PLAN;
-    // the kernel loads two chunks past the segment it is working on
-    for (int i = 0; i < 3 * SCONV_FLAT_CHUNK; ++i) out.pairs.push_back(pad_entry);
+    // the kernel loads two chunks past the segment it is working on, and warms L2 with what follows those
+    for (int i = 0; i < 3 * SCONV_FLAT_CHUNK + SCONV_FLAT_WARM_BYTES / 8; ++i) out.pairs.push_back(pad_entry);
     // store offsets of the positions a group of cg waves covers
     const int npos = t.p.cg * t.p.t * 64;
     out.store_tbl.assign(npos, -1);

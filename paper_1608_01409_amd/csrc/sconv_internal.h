@@ -85,6 +85,9 @@ inline bool is_flat_kernel(int kernel) { return kernel == 3 || kernel == 4; }
 //   high 32 bits (LDS byte offset / 16) << 16 | (row index inside the slot * t * 4)
 // Padding entries have value +0.0 and point at the zero page.
 #define SCONV_FLAT_CHUNK 8
+// The kernel warms L2 with this many bytes of the stream beyond the point its scalar loads have reached (which is
+// up to two chunks past a segment's end): the stream array carries that much padding behind its last segment.
+#define SCONV_FLAT_WARM_BYTES 4096
 struct PackedFlat {
     LdsTiling t;
     std::vector<uint64_t> pairs;

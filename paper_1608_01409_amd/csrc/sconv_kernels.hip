@@ -258,6 +258,7 @@ struct Lds2Args {
     // strided layers staged straight from the caller's input (phase_stride > 1), else {huge, 1, 0, 0}: read by the asm
     int blocks_per_phase, phase_stride, src_row_bytes, phase_span_bytes; // phase_span = the group's channels of one phase
     int phase_cg;            // real channels per phase of a group
+    int wide;                // the four images of a cell are adjacent in memory (16-byte aligned): staged a cell per lane
     FastDiv d_pcg, d_pstride;
     FastDiv d_units, d_splits, d_bands, d_nkt, d_cg, d_wl, d_strip; // the divisors of the index arithmetic below
 };
@@ -271,6 +272,7 @@ static_assert(offsetof(Lds2Args, store_tbl) == SCONV_LDS2_OFF_TBL, "asm reads st
 static_assert(offsetof(Lds2Args, cb) == SCONV_LDS2_OFF_CONSTS, "asm reads eight constants from here");
 static_assert(offsetof(Lds2Args, img_stride_bytes) == SCONV_LDS2_OFF_CONSTS + 28, "layout of the constants");
 static_assert(offsetof(Lds2Args, blocks_per_phase) == SCONV_LDS2_OFF_PHASE, "asm reads the four phase constants from here");
+static_assert(SCONV_LDS2_WARM_BYTES == SCONV_FLAT_WARM_BYTES, "the host pads the stream by what the kernel reads ahead");
 static_assert(offsetof(Lds2Args, phase_span_bytes) == SCONV_LDS2_OFF_PHASE + 12, "layout of the phase constants");
 
 constexpr unsigned kSkipLane = 0xFFFFFFFFu; // lane past the end of a plane: writes nothing
@@ -318,11 +320,15 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     const int wslot = __builtin_amdgcn_readfirstlane((g * a.nkt + kt) * a.rg + rgi);
     const int nimg = min(4, a.N - n0);
 
-    // per-lane source offsets of the slabs this wave stages, relative to channel 0 of image n0
+    // per-lane source offsets of the slabs this wave stages, relative to channel 0 of image n0.  A slab is what
+    // one load instruction fills: 64 floats (16 cells, a float per lane), or 64 cells (a cell per lane) where the
+    // four images of a cell are 16 adjacent, aligned bytes of the input (a.wide: feature-major activations).
+    const bool wide = a.wide != 0;
+    const int n_slabs = wide ? (a.plane_floats + 255) >> 8 : a.n_slabs;
     unsigned voff[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int f = (wave + j * n_waves) * 64 + lane;
+        const int f = wide ? ((wave + j * n_waves) * 64 + lane) * 4 : (wave + j * n_waves) * 64 + lane;
         const int cell = f >> 2, img = f & 3;
         const int Y = fdiv(cell, a.d_wl), X = cell - Y * a.Wl;
         if (a.phase_stride > 1) {
@@ -343,7 +349,7 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
     }
     int nslab = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) nslab += (wave + j * n_waves < a.n_slabs) ? 1 : 0;
+    for (int j = 0; j < 4; ++j) nslab += (wave + j * n_waves < n_slabs) ? 1 : 0;
 
     // the zero page behind each block buffer: cleared here, never written again
     {
@@ -401,13 +407,14 @@ __global__ void __launch_bounds__(1024) sconv_lds2_kernel(const Lds2Args a)
         px0 = (unsigned)px;
     }
     const unsigned long long bias = (unsigned long long)a.bias;
-    const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane(a.relu ? 1 : 0);
+    const unsigned flags = (unsigned)__builtin_amdgcn_readfirstlane((a.relu ? 1 : 0) | (wide ? 2 : 0));
+    const unsigned slab_bytes = wide ? 1024u : 256u;
     Lds2Asm<T, R, STEP, FLOW>::run((unsigned long long)__builtin_amdgcn_kernarg_segment_ptr(), rsrc,
                        a.seg + ((size_t)wslot * a.nblk + blk0) * 2,
                        a.row_of + (size_t)wslot * R,
                        __builtin_amdgcn_readfirstlane((unsigned)op), __builtin_amdgcn_readfirstlane((unsigned)(op >> 32)),
                        (unsigned)__builtin_amdgcn_readfirstlane(soff0), (unsigned)nimg, lim,
-                       __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)(wave * 256), (unsigned)(n_waves * 256),
+                       __builtin_amdgcn_readfirstlane(ldsbase), (unsigned)wave * slab_bytes, (unsigned)n_waves * slab_bytes,
                        (unsigned)__builtin_amdgcn_readfirstlane(nslab), (unsigned)(cell0 * 16), voff[0],
                        voff[1], voff[2], voff[3], (unsigned)((cgi * T * 64 + lane) * 4),
                        (unsigned)__builtin_amdgcn_readfirstlane(nch_here), (unsigned)__builtin_amdgcn_readfirstlane(nblk_here),
@@ -808,6 +815,10 @@ int launch_lds2(const sconv_desc &d, const LdsTiling &t, const DeviceLds &dev, c
         a.d_pcg = make_fastdiv(t.phase_cg, g.Cg);
         a.d_pstride = make_fastdiv(lay.phase_stride, lay.phase_stride * lay.phase_stride);
     }
+    // a cell per lane instead of a float per lane where a cell's four images are 16 adjacent, aligned bytes and
+    // no lane needs the zero fill of the padding
+    a.wide = (lay.phase_stride == 1 && d.pad == 0 && lay.in_pos == 4 && lay.in_img == 1 && lay.in_ch % 4 == 0 && lay.in_tile % 4 == 0 &&
+              reinterpret_cast<uintptr_t>(in) % 16 == 0 && N % 4 == 0) ? 1 : 0;
     // with several parts the kernel stores partial sums into the workspace `out` points to, part after part,
     // and the reduction that follows applies the epilogue
     a.split_stride = a.splits > 1 ? split_stride : 0;
