@@ -520,7 +520,33 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
                     emit(f"{instr} v{RING0 + t}, v{ACC0 + (i * T + t) * 4 + e}, s[{SX0}:{SX1}]")
                 emit(f"{rowend}:")
 
-    store_all("global_store_dword")
+    if T <= len(MASKS):
+        # Where the four images of a position are adjacent in the output (feature-major activations: image stride
+        # 4 bytes) and all four exist, a lane stores its four sums of a row with one instruction.
+        narrow, stored = label("narrow"), label("stored")
+        emit(f"s_cmp_eq_u32 s{SPTR + 1}, 4")
+        emit(f"s_cbranch_scc0 {narrow}")
+        emit(f"s_cmp_eq_u32 {OP['nimg']}, 4")
+        emit(f"s_cbranch_scc0 {narrow}")
+        for t in range(T):
+            emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
+            emit(f"v_cmp_gt_u32_e32 vcc, {OP['lim']}, v{RING0 + t}")
+            emit(f"s_mov_b64 s[{MASKS[t]}:{MASKS[t] + 1}], vcc")
+        for i in range(R):
+            rowend = label("rowend")
+            emit(f"s_cmp_lt_i32 s{KROW + i}, 0")
+            emit(f"s_cbranch_scc1 {rowend}")
+            for t in range(T):
+                a0 = ACC0 + (i * T + t) * 4
+                emit(f"s_mov_b64 exec, s[{MASKS[t]}:{MASKS[t] + 1}]")
+                emit(f"global_store_dwordx4 v{RING0 + t}, v[{a0}:{a0 + 3}], s[{BASE + 2 * i}:{BASE + 2 * i + 1}]")
+            emit(f"{rowend}:")
+        emit(f"s_branch {stored}")
+        emit(f"{narrow}:")
+        store_all("global_store_dword")
+        emit(f"{stored}:")
+    else:
+        store_all("global_store_dword")
     emit(f"s_mov_b64 exec, s[{SEXEC}:{SEXEC + 1}]")
 
     vregs = {"lane_byte", "voff0", "voff1", "voff2", "voff3", "tbloff"}
