@@ -592,7 +592,7 @@ static int fc_mapping(const sconv_csr *h, int N, sconv_desc &kd, int &tiles)
 static sconv_plan fc_request(const sconv_csr *h)
 {
     sconv_plan req = h->requested;
-    req.kernel = req.kernel == 4 ? 4 : 3;
+    req.kernel = (req.kernel == 3 || req.kernel == 4) ? req.kernel : 0; // tiles of four images: a flat-stream variant either way
     req.nt = 4;
     req.band = 0;
     req.strip = 0;
@@ -650,7 +650,7 @@ static int plan_fc(sconv_csr *h, int N, const sconv_plan *force = nullptr)
     for (size_t j = 0; j < kc.off.size(); ++j) kc.off[j] = h->canon.off[j] * kd.W; // feature c = row c of the wide image
     const double avg = kd.K ? (double)kc.val.size() / kd.K : 0.0;
     LdsTiling t;
-    rc = make_lds_tiling(kd, force ? *force : fc_request(h), 4 * tiles, avg, t);
+    rc = make_lds_tiling(kd, force ? *force : fc_request(h), 4 * tiles, avg, t, 0, true);
     if (rc) return rc;
     t.out_pos = 4; // the four images of a cell are consecutive in the output row
     rc = pack_flat(kd, kc, t, h->fc_flat);
@@ -848,7 +848,7 @@ extern "C" int sconv_fc_tune(sconv_csr *h, const float *in_t, float *out_t, int3
         if (rc) return rc;
         const double avg = kd.K ? (double)h->canon.val.size() / kd.K : 0.0;
         std::vector<LdsTiling> cands;
-        rc = rank_lds_tilings(kd, fc_request(h), 4 * tiles, avg, clamp_plans(max_plans), cands);
+        rc = rank_lds_tilings(kd, fc_request(h), 4 * tiles, avg, clamp_plans(max_plans), cands, 0, true);
         if (rc) return rc;
         int best = -1;
         StashRoom room(h, cands.size());

@@ -256,7 +256,10 @@ static double tiling_cost(const sconv_desc &d, const LdsTiling &t, int N, double
 // The same for the flat-stream kernel, in microseconds at 2.4 GHz; constants fitted to measured plan sweeps
 // of the AlexNet layers at batch 256 (useful issue efficiency of the multiply-add loop, cost of a channel
 // block's barrier and pipeline refill, cost of a workgroup's prologue and stores).
-static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, double avg_row_nnz)
+// wide: the layer's input is staged a cell per lane and its output stored four images at a time (feature-major
+// activations): a block lands sooner and the stores of a workgroup take a fraction of the time.
+static const double kWideFixed = 0.7;
+static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, double avg_row_nnz, bool wide)
 {
     const Geometry g = geometry(d);
     const int splits = std::max(1, t.p.splits);
@@ -283,32 +286,36 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     // landing time, which binds at low density (measured: 3.3 us for 50 KB, 4.5 us for 74 KB per CU).
     const bool flow = t.p.kernel == 4;
     const double sync = flow ? 100.0 : 800.0 / m;
-    const double landing = 4000.0 + m * block_bytes / 11.0;
+    // (a cell per lane: 0.7 us for the first bytes of a block, then 37 bytes per clock and CU)
+    const double landing = wide ? 1700.0 + m * block_bytes / 37.0 : 4000.0 + m * block_bytes / 11.0;
     const double compute_block = m * simd_clk / eff / blocks;
     const double per_block = std::max(compute_block + sync + m * block_bytes / 120.0, landing);
-    double group = blocks * per_block + (m >= 2 ? (t.p.waves >= 8 ? 8000.0 : 10500.0) : 14000.0);
+    double group = blocks * per_block + (m >= 2 ? (t.p.waves >= 8 ? 8000.0 : 10500.0) : 14000.0) * (wide ? kWideFixed : 1.0);
     // Measured: the flow variant is the slower one (3-12 %) where a second workgroup on the CU already fills
     // the barrier's gaps and the blocks are only a few channels deep, where a block's arithmetic does not outlast its loads by a margin (its loads have
     // only the first chunks of a block to land in), and where there are too few blocks to rotate buffers.
     if (flow && ((m >= 2 && t.p.cb < 8) || blocks < 3 || compute_block < 1.5 * landing)) group *= 1.1;
+    // (measured on the fully connected layers: with 16 waves 5-7 % behind the barrier variant and its larger blocks,
+    // with 8 waves up to 10 % ahead)
+    else if (flow && wide && t.p.waves >= 16) group *= 1.12;
     if (t.p.t >= 7) group /= 0.88;                            // shapes short of address registers
     double us = std::ceil(cu_wgs / m) * group / 2400.0;
     if (splits > 1) {
         // every part stores its partial results and a launch of its own adds them up
         const double out_bytes = 4.0 * N * d.K * g.OH * g.OW;
-        us += 4.0 + splits * (out_bytes / 3.5e6 + 0.3); // the reduction reads every part: bandwidth, and latency per part
+        us += 4.0 + splits * (out_bytes / (wide ? 6.0e6 : 3.5e6) + 0.3); // the reduction reads every part: bandwidth, and latency per part
     }
     return us;
 }
 
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
-                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg = 0);
+                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg = 0, bool wide = false);
 // whether the library, left to itself, considers the flow variant of the flat-stream kernel
 static const bool kFlowByDefault = true;
 
-int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg)
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg, bool wide)
 {
-    return search_lds_tilings(d, req, N_hint, avg_row_nnz, out, nullptr, phase_cg);
+    return search_lds_tilings(d, req, N_hint, avg_row_nnz, out, nullptr, phase_cg, wide);
 }
 
 static bool same_tiling(const sconv_plan &a, const sconv_plan &b)
@@ -318,11 +325,11 @@ static bool same_tiling(const sconv_plan &a, const sconv_plan &b)
 }
 
 int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
-                     std::vector<LdsTiling> &out, int phase_cg)
+                     std::vector<LdsTiling> &out, int phase_cg, bool wide)
 {
     std::vector<std::pair<double, LdsTiling>> all;
     LdsTiling best;
-    const int rc = search_lds_tilings(d, req, N_hint, avg_row_nnz, best, &all, phase_cg);
+    const int rc = search_lds_tilings(d, req, N_hint, avg_row_nnz, best, &all, phase_cg, wide);
     if (rc) return rc;
     std::stable_sort(all.begin(), all.end(), [](const std::pair<double, LdsTiling> &a, const std::pair<double, LdsTiling> &b) {
         return a.first < b.first;
@@ -338,7 +345,7 @@ int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, dou
 }
 
 static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out,
-                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg)
+                              std::vector<std::pair<double, LdsTiling>> *all, int phase_cg, bool wide)
 {
     const Geometry g = geometry(d);
     if (d.stride != 1) return SCONV_ERR_PLAN;
@@ -407,7 +414,7 @@ static int search_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_
                         LdsTiling t;
                         if (fill_tiling(d, p, t, phase_cg) != SCONV_OK) continue;
                         if (!req.splits && t.p.splits != sp) continue; // the same as a smaller choice
-                        const double c = flat ? tiling_cost_flat(d, t, N_hint, avg_row_nnz)
+                        const double c = flat ? tiling_cost_flat(d, t, N_hint, avg_row_nnz, wide)
                                                    : tiling_cost(d, t, N_hint, avg_row_nnz);
                         if (all) all->emplace_back(c, t);
                         if (best < 0 || c < best) {

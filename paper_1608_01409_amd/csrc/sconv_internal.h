@@ -119,10 +119,13 @@ int build_canonical_from_arrays(const sconv_desc &d, const int32_t *rowptr, cons
 // batch size the choice is tuned for.  Returns SCONV_ERR_PLAN if the layer cannot use it.
 // phase_cg > 0: d is the stride-1 form of a strided layer without padding, with that many real channels per
 // phase; tilings whose blocks hold whole phases' channels can then be staged without the phase-image pass.
-int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg = 0);
+// wide: the input will be staged a cell per lane and the output stored four images at a time (feature-major
+// activations); the cost model prices the landing of a block and the stores accordingly.
+int make_lds_tiling(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, LdsTiling &out, int phase_cg = 0,
+                    bool wide = false);
 // The max_out distinct tilings the cost model ranks best, best first (out[0] is make_lds_tiling's choice).
 int rank_lds_tilings(const sconv_desc &d, const sconv_plan &req, int N_hint, double avg_row_nnz, int max_out,
-                     std::vector<LdsTiling> &out, int phase_cg = 0);
+                     std::vector<LdsTiling> &out, int phase_cg = 0, bool wide = false);
 // p.kernel selects the shape list: 1 = per-row streams, 3 = flat streams (nt must be 4)
 bool lds_kernel_available(int vec, int t, int rows_w);
 
