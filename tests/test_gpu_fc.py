@@ -104,3 +104,58 @@ def test_batches_the_kernel_cannot_take_are_refused():
     with pytest.raises(B.SconvError) as e:
         B.sconv_fc_forward(h, x)
     assert e.value.status == B.ERR["BATCH"]
+
+
+@pytest.mark.parametrize("plan,N", [
+    (dict(kernel=3, waves=16, rows_w=8, t=1), 256), (dict(kernel=4, waves=16, rows_w=8, t=1), 256),
+    (dict(kernel=3, waves=8, rows_w=12, t=1), 256), (dict(kernel=4, waves=8, rows_w=12, t=1), 252),
+    (dict(kernel=3, waves=8, rows_w=16, t=1), 256), (dict(kernel=4, waves=4, rows_w=16, t=1), 64),
+    (dict(kernel=3, waves=16, rows_w=8, cg=1), 512), (dict(kernel=4, waves=16, rows_w=8, cg=2), 1024),
+    (dict(kernel=3, waves=16, rows_w=16, cg=4), 1024), (dict(kernel=3, waves=8, rows_w=8, t=1, splits=4, cb=5), 256),
+])
+def test_explicit_tilings_of_both_variants(plan, N):
+    """Every one-chunk shape, several chunks per wave (batches of 512 and 1024 with one column group), column
+    groups and channel splits, barrier and flow variant."""
+    _, used, _ = run(300, 1100, N, 0.12, seed=21, bias_on=True, relu=True, plan=plan, empty_rows=(17,))
+    for key, v in plan.items():
+        assert used[key] == v, (key, used)
+    assert used["t"] * used["cg"] == -(-N // 256), used
+
+
+def test_activations_that_are_not_16_byte_aligned():
+    """Aligned activations are staged a cell (four images, 16 bytes) per lane, others a float per lane; the sums
+    are formed in the same order either way, so the two results agree bit for bit."""
+    K, C, N = 130, 520, 256
+    w, x_t, _ = case(K, C, N, 0.1, seed=22)
+    h = B.sconv_create_csr(B.fc_layer(C, K), w.reshape(K, C, 1, 1))
+    aligned = torch.from_numpy(x_t).cuda()
+    assert aligned.data_ptr() % 16 == 0
+    flat = torch.empty(C * N + 1, device="cuda")
+    shifted = flat[1:].view(C, N)
+    shifted.copy_(aligned)
+    assert shifted.data_ptr() % 16 == 4 and shifted.is_contiguous()
+    say("fc aligned / shifted activations")
+    a = B.sconv_fc_forward(h, aligned).cpu().numpy()
+    oflat = torch.full((K * N + 1,), float("nan"), device="cuda")
+    b = B.sconv_fc_forward(h, shifted, None, False, oflat[1:].view(K, N)).cpu().numpy()
+    ref, ab = so.spmdm(w, x_t)
+    assert np.all(np.abs(a.astype(np.float64) - ref) <= TOL * ab)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("N", [8, 6, 3])
+def test_convolution_whose_images_are_adjacent_in_the_output(oracle, N):
+    """K = 1 with a single output position: consecutive images are 4 bytes apart in the output, the case in which
+    the flat-stream kernel stores the four images of a cell with one instruction (full tiles only)."""
+    from paper_1608_01409_amd import workloads as wl
+    layer = wl.Layer("one_output", C=24, H=3, W=3, K=1, R=3, S=3, stride=1, pad=0, groups=1)
+    rng = np.random.default_rng(23)
+    w = np.where(rng.random((1, 24, 3, 3)) < 0.4, rng.standard_normal((1, 24, 3, 3)), 0).astype(np.float32)
+    x = rng.standard_normal((N, 24, 3, 3)).astype(np.float32)
+    say(f"conv K=1 1x1 output N={N}")
+    h = B.sconv_create_csr(layer, w, dict(kernel=3))
+    out = torch.full((N, 1, 1, 1), float("nan"), device="cuda")
+    B.sconv_forward(h, torch.from_numpy(x).cuda(), out)
+    got = out.cpu().numpy().astype(np.float64)
+    ref, ab, _ = oracle.sparse_conv(layer, w, x)
+    assert np.all(np.abs(got - ref) <= TOL * ab), (got.ravel(), ref.ravel())
