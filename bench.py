@@ -101,7 +101,7 @@ def main() -> int:
     t1 = time.perf_counter()
     if args.dispatch_log:
         def n_kernels(L):
-            return 1 + (1 if L["plan"]["splits"] > 1 else 0) + (1 if L["layer"].stride > 1 and L["plan"]["kernel"] != 2 else 0)
+            return 1 + (1 if L["plan"]["splits"] > 1 else 0) + (1 if L["layer"].stride > 1 and not (L["plan"]["kernel"] == 2 or (L["layer"].pad == 0 and L["plan"]["kernel"] in (3, 4))) else 0)
         calls = [dict(layer=L["name"], kernels=n_kernels(L), phase=ph) for ph, n in (("warmup", args.warmup), ("timed", args.steps))
                  for _ in range(n) for L in layers]
         json.dump(dict(config="bench.py: AlexNet conv2-5, batch 256, density 0.10" + (f", tilings tuned (--tune {args.tune})" if args.tune > 0 else ""),

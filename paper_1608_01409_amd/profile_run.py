@@ -35,7 +35,7 @@ def conv_layers(cfg_index, cases, skewed=False):
         o = torch.empty((N, layer.K, layer.OH, layer.OW), dtype=torch.float32, device="cuda")
         B.sconv_forward(h, xd, o)                      # settles the tiling for this batch size
         plan = B.sconv_csr_info(h)["plan"]
-        kernels = 1 + (1 if plan["splits"] > 1 else 0) + (1 if layer.stride > 1 and plan["kernel"] != 2 else 0)
+        kernels = 1 + (1 if plan["splits"] > 1 else 0) + (1 if layer.stride > 1 and not (plan["kernel"] == 2 or (layer.pad == 0 and plan["kernel"] in (3, 4))) else 0)
         nnz = B.sconv_csr_info(h)["nnz"]
         out.append(dict(name=name, run=(lambda h=h, xd=xd, o=o: B.sconv_forward(h, xd, o)), kernels=kernels, plan=plan, N=N,
                         flops=2.0 * nnz * layer.OH * layer.OW * N,
