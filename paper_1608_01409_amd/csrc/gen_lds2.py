@@ -34,8 +34,11 @@ Two ways of keeping the waves of a workgroup in step with the block buffers (tem
            those loads have landed, adds 1 to an LDS counter S[b+1].  A wave starts block b when S[b]
            shows every wave's share of block b present.  A wave that signals S[b+1] is inside block b, so
            S[b+1] complete also means every wave has left block b-1: its buffer may be overwritten with
-           block b+2.  Waves drift up to about half a block apart; nobody waits for the slowest wave at
-           every block.  (FLOW_LOOK = 2 is the same with four buffers, loads two blocks ahead and the
+           block b+2.  Only the first few waves of a workgroup have a share (the kernel hands the slabs to
+           the waves the SIMDs serve first, which run ahead); a wave without one adds its 1 on entering
+           block b, so S[b+1] fills when the early waves' loads are in and the late waves have entered
+           block b: waves drift up to a block apart, and nobody waits for the slowest wave to be well into a
+           block.  (FLOW_LOOK = 2 is the same with four buffers, loads two blocks ahead and the
            landing reported when the block during which they were issued is finished: measured slower,
            the blocks being a quarter shorter.)
 """
@@ -373,7 +376,19 @@ def gen_shape(T: int, R: int, D: int, batch: bool, step: int, flow: bool = False
         emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
         stage(STGT)
         if FLOW_LOOK == 1:
-            emit(f"s_mov_b32 vcc_lo, {SIGNAL_AFTER}")      # report the landing that many first-of-three chunks on
+            # A wave with a share of the block reports its landing that many first-of-three chunks on.  A wave without
+            # one (the later waves of a workgroup, which the SIMD's oldest-first arbitration makes the slow ones) has
+            # nothing to wait for and reports at once: the counter then fills when the early waves' loads have
+            # landed and the late waves have merely entered this block, not when they are three chunks into it.
+            mine, told = label("mine"), label("told")
+            emit(f"s_cmp_lg_u32 {OP['nslab']}, 0")
+            emit(f"s_cbranch_scc1 {mine}")
+            signal(4)
+            emit("s_mov_b32 vcc_lo, 0")
+            emit(f"s_branch {told}")
+            emit(f"{mine}:")
+            emit(f"s_mov_b32 vcc_lo, {SIGNAL_AFTER}")
+            emit(f"{told}:")
     else:
         emit(f"s_sub_u32 s{STGT}, s{SSTRIDE}, s{SBUF}")
         emit(f"s_add_u32 s{STGT}, s{STGT}, {OP['ldsbase']}")
