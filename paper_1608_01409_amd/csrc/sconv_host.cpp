@@ -273,7 +273,9 @@ static double tiling_cost_flat(const sconv_desc &d, const LdsTiling &t, int N, d
     const double m = std::min((double)wpc, cu_wgs);           // ... m of them side by side
     const double wps = t.p.waves * m / 4.0;                   // waves per SIMD
     double eff = wps >= 4 ? 0.78 : wps >= 3 ? 0.72 : wps >= 2 ? 0.68 : 0.42;
-    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.93; // shallow read-ahead ring
+    // a shallow read-ahead ring (8 rows of 3 chunks leave registers for one entry ahead only) costs little: measured
+    // on the 27x27 layer, 8 rows per wave beat 6 by 5 % in either variant, the longer streams outweighing it
+    if (lds2_depth(t.p.t, t.p.rows_w) * t.p.t < 6) eff *= 0.99;
     const double simd_clk = t.p.waves * entries * (4.0 * t.p.t + 1.7); // VALU clocks per SIMD, one workgroup
     // per channel block: the barrier and the refill of the read pipeline, which a second workgroup on the CU
     // fills, and what the staging of the block (L2 to LDS, every workgroup its own copy) takes from the loop;
