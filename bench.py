@@ -33,6 +33,9 @@ def main() -> int:
     ap.add_argument("--tune", type=int, default=8,
                     help="during set-up let sconv_tune time this many candidate tilings per layer and keep the "
                          "fastest, as a deployment of the library would (0: the cost model's choice, untimed)")
+    ap.add_argument("--layer-events-every", type=int, default=4,
+                    help="time the individual kernels (an event pair around each) on every M-th timed step; the pairs "
+                         "cost stream time, so M = 1 lengthens every step by a few percent")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for "
                          "scaling the HBM byte counters of a profiler run)")
@@ -80,9 +83,13 @@ def main() -> int:
             if events is not None:
                 events[i][1].record(stream)
 
-    # events first: nothing but the warm-up steps themselves runs between set-up and the timed steps
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-          for _ in range(args.steps)]
+    # events first: nothing but the warm-up steps themselves runs between set-up and the timed steps.  An event pair
+    # around a kernel keeps the next launch from starting behind it (~3 us of stream time per pair: on every step that
+    # is 3.5 % of the step), so the kernels are timed on every M-th timed step only; every step gets one event at its start.
+    every = max(1, args.layer_events_every)
+    timed_steps = [k for k in range(args.steps) if k % every == 0]
+    ev = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers] for k in timed_steps}
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -96,7 +103,9 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(ev[k])
+        step_ev[k].record(stream)
+        step(ev.get(k))
+    step_ev[args.steps].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     if args.dispatch_log:
@@ -115,7 +124,7 @@ def main() -> int:
 
     per_layer = []
     for i, L in enumerate(layers):
-        ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
+        ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in timed_steps]))
         tf = L["flops"] / (ms * 1e-3) / 1e12
         per_layer.append(dict(layer=L["name"], kernel_us=round(ms * 1e3, 2), tflops=round(tf, 3),
                               effective_tflops=round(L["dense_flops"] / (ms * 1e-3) / 1e12, 2),
@@ -148,7 +157,7 @@ def main() -> int:
 
     # how steady the timed region was: the GPU's power management settles over the first tens of milliseconds
     # of load, and steps taken during that time run up to 15 % slower than later ones
-    step_us = [ev[k][0][0].elapsed_time(ev[k][-1][1]) * 1e3 for k in range(args.steps)]
+    step_us = [step_ev[k].elapsed_time(step_ev[k + 1]) * 1e3 for k in range(args.steps)]
     q = max(1, args.steps // 4)
     steadiness = dict(first_quarter_us=round(float(np.mean(step_us[:q])), 1), last_quarter_us=round(float(np.mean(step_us[-q:])), 1))
 
@@ -188,6 +197,7 @@ def main() -> int:
         "config": {"workload": "AlexNet conv2-conv5, batch 256, fp32, Bernoulli masks at density 0.10", "global_batch": 256,
                    "tiling": f"fastest of {args.tune} candidates timed during set-up (sconv_tune)" if args.tune > 0 else "cost model",
                    "timed_region": steadiness,
+                   "kernel_timing": f"HIP event pairs around every kernel on timed steps {timed_steps[:3]}... ({len(timed_steps)} of {args.steps})",
                    "dense_equivalent_gflops": round(sum(L["dense_flops"] for L in layers) / (ms_per_step * 1e-3) / 1e9, 1)},
         "roofline": roofline, "cpu_baseline": cpu}))
     return 0
