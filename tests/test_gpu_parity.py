@@ -190,6 +190,36 @@ def test_random_layers_automatic_plan(oracle, seed):
     assert info["plan"]["kernel"] == 4
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_random_layers_with_many_channels_both_flat_variants(oracle, seed):
+    """Up to 40 input channels per group and 70 rows, so that a workgroup walks several channel blocks, with the
+    barrier or the flow variant forced, 4 to 16 waves and sometimes a channel split: the block ring, the landing
+    counters, the staging by the first waves and the reduction of partial results on shapes nobody chose.
+    A tiling the library refuses for the drawn layer is a skipped case, not a failure."""
+    rng = np.random.default_rng(71000 + seed)
+    groups = int(rng.choice([1, 1, 2]))
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    stride, pad = int(rng.choice([1, 1, 1, 2, 4])), int(rng.integers(0, 3))
+    H = max(int(rng.integers(1, 40)), R - 2 * pad, 1)
+    W = max(int(rng.integers(1, 40)), S - 2 * pad, 1)
+    layer = wl.small_layer("rnd", C=groups * int(rng.integers(1, 40)), H=H, W=W, K=groups * int(rng.integers(1, 70)),
+                           R=R, S=S, stride=stride, pad=pad, groups=groups)
+    N = int(rng.choice([4, 5, 8, 12, 17, 33, 64]))
+    x, w = rand_case(layer, N, float(rng.choice([0.03, 0.2, 0.6, 1.0])), seed=72000 + seed)
+    plan = dict(kernel=int(rng.choice([3, 4, 4])))
+    if rng.random() < 0.5:
+        plan["waves"] = int(rng.choice([4, 8, 16]))
+    if rng.random() < 0.3:
+        plan["splits"] = int(rng.choice([2, 3]))
+    try:
+        _, info = check(layer, w, x, oracle, plan, what=f"random-many-channels-{seed}")
+    except B.SconvError as e:
+        if e.status == B.ERR["PLAN"]:
+            pytest.skip(f"tiling {plan} not runnable for {layer}")
+        raise
+    assert info["plan"]["kernel"] == plan["kernel"]
+
+
 SHAPES = [
     dict(C=8, H=27, W=27, K=16, R=5, S=5, stride=1, pad=2, groups=2),
     dict(C=6, H=28, W=28, K=12, R=3, S=3, stride=1, pad=1, groups=1),
